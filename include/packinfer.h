@@ -1,0 +1,234 @@
+/*
+ * packinfer.h -- C ABI of the MI355X (gfx950) packed-attention library.
+ *
+ * The calls follow the problem statement of the PackInfer paper (Alg. 1,
+ * inputs and outputs; Sec. 3.1 packed computation; Sec. 3.2 packed I/O):
+ *
+ *   pk_pack_plan            lengths, prefix families, budget C -> groups S_g,
+ *                           offset tables O_g                    (Alg. 1)
+ *   pk_kv_reorganize        paged KV -> group-contiguous buffers B_g
+ *                           (Alg. 1 Part 2, Sec. 3.2 consolidation)
+ *   pk_packed_prefill_attn  causal attention over the packed query-key
+ *                           regions of each group                (Sec. 3.1)
+ *   pk_packed_decode_attn   one query per request over B_g, shared prefix
+ *                           read once per group, split-KV + LSE merge
+ *                           (Sec. 3.2; Sec. 1 lossless merge)
+ *   pk_padded_*             per-request padded execution, the in-run
+ *                           comparison the paper argues against (Sec. 2.2)
+ *
+ * Conventions
+ *   - "host" / "device" is stated for every pointer.  Device buffers are
+ *     caller-owned; the library never allocates or frees device memory.
+ *   - Kernels are enqueued on the caller's hipStream_t (passed as void*,
+ *     NULL = default stream) and the call returns without synchronising.
+ *     Small integer tables are copied host->device on that stream when a
+ *     plan is first used with a workspace (see pk_plan_bind).
+ *   - All tensors are in CALLER REQUEST ORDER; the permutation into groups
+ *     is internal.
+ *   - Return value: PK_OK (0) or a negative PK_E* code; the message is
+ *     available from pk_last_error() (thread-local).  Arguments are checked
+ *     before anything is launched.  Nothing throws or aborts.
+ *   - dtype: PK_BF16 (MFMA path) or PK_F32 (plain-FMA debug path).
+ *     out_dtype: PK_BF16 or PK_F32 for the attention outputs.
+ */
+#ifndef PACKINFER_H
+#define PACKINFER_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { PK_OK = 0, PK_EINVAL = -1, PK_ENOMEM = -2, PK_EUNSUPPORTED = -3, PK_EHIP = -4 };
+enum { PK_BF16 = 0, PK_F32 = 1 };
+
+/* Layout constants of the group-contiguous buffer. */
+#define PK_GROUP_ALIGN 32      /* group bases are multiples of this many tokens */
+#define PK_KV_BLOCK    32      /* tokens per tile of the bf16 buffer layout     */
+
+typedef struct pk_plan pk_plan; /* opaque; host memory owned by the library */
+
+/* ------------------------------------------------------------------------
+ * pk_pack_plan -- Alg. 1 Part 1 (greedy length-balanced grouping under the
+ * feasibility test of Eq. 2, token term) and the bookkeeping of Part 2
+ * (prefix-first layout, offset tables O_g).  Deterministic, integer only.
+ *
+ *   kv_lens     host [n]  L_i: KV tokens request i attends to (incl. the
+ *                         current token); > 0
+ *   q_lens      host [n]  query rows of request i; NULL = kv_lens (plain
+ *                         prefill); 1 = decode; < kv_len = chunked prefill.
+ *                         Queries are the last q_len positions.
+ *   prefix_ids  host [n]  family id (>= 0) or -1; NULL = no families
+ *   prefix_lens host [n]  shared-prefix length, equal inside a family,
+ *                         0 <= prefix_len <= kv_len; NULL iff prefix_ids NULL
+ *   n                     number of requests (0 is allowed: empty plan)
+ *   token_budget          C > 0, unique KV tokens per group (Sec. 3.2)
+ *   headroom              delta >= 0 tokens reserved after every suffix
+ *   out                   receives the plan; free with pk_plan_destroy
+ *
+ * Grouping rules: a family is one atomic item of length L_P + sum(L_Q); a
+ * family longer than C is cut in member order into the fewest consecutive
+ * sub-families that fit; items are sorted by (length desc, lowest member
+ * index), the least-loaded group (lowest index on ties) takes the item if it
+ * stays within C, otherwise a new group is opened; an item longer than C is
+ * alone in its group; empty groups are dropped.
+ * Errors: PK_EINVAL for any violated precondition.
+ */
+int pk_pack_plan(const int32_t* kv_lens, const int32_t* q_lens,
+                 const int32_t* prefix_ids, const int32_t* prefix_lens,
+                 int32_t n, int64_t token_budget, int32_t headroom, pk_plan** out);
+
+void pk_plan_destroy(pk_plan* plan);
+
+/* Read-only accessors (host). */
+int32_t pk_plan_num_requests(const pk_plan* plan);
+int32_t pk_plan_num_groups(const pk_plan* plan);
+/* Tokens of the whole buffer (all groups, each base rounded up to
+ * PK_GROUP_ALIGN; the total is a multiple of PK_KV_BLOCK). */
+int64_t pk_plan_buf_tokens(const pk_plan* plan);
+/* Unique KV tokens summed over groups: the I/O volume M of Eq. 5 without
+ * headroom. */
+int64_t pk_plan_unique_tokens(const pk_plan* plan);
+
+/* Canonical serialisation, int32 words:
+ *   magic 0x504B504C, version 1, n, G, C lo, C hi, headroom, PK_GROUP_ALIGN,
+ *   buf_tokens lo, hi, then per group:
+ *   load lo, hi, buf_tokens lo, hi, buf_base lo, hi, n_members, then per
+ *   member (layout order): request, prefix_off, L_P, suffix_off, L_Q
+ *   (offsets in tokens relative to the group base) -- the tuple O_g[i] of
+ *   Alg. 1.
+ * pk_plan_serialized_words returns the word count; pk_plan_serialize copies
+ * them to host `out` (capacity `cap` words) and returns the count or
+ * PK_EINVAL if cap is too small. */
+int64_t pk_plan_serialized_words(const pk_plan* plan);
+int64_t pk_plan_serialize(const pk_plan* plan, int32_t* out, int64_t cap);
+
+/* ------------------------------------------------------------------------
+ * Sizes of the caller-allocated device buffers.
+ *
+ * pk_kv_buf_bytes: bytes of the group-contiguous KV buffer.
+ *   PK_BF16 layout: [Hkv][buf_tokens / 32] tiles; one tile holds 32 tokens of
+ *   one KV head: first the K part (32*d bf16), then the V part (32*d bf16).
+ *     K part: two sub-tiles u (tokens 16u..16u+15), each d/32 steps s of
+ *       64 chunks l of 8 bf16: chunk (u,s,l)[j] = K[16u + l%16][32s + 8(l/16) + j]
+ *     V part: d/16 column blocks t of 64 chunks l of 8 bf16:
+ *       chunk (t,l)[j] = V[kappa(l/16, j)][16t + l%16],
+ *       kappa(g, j) = 4g + j for j < 4, 16 + 4g + (j-4) otherwise.
+ *   (This is the operand order of the 16x16x32 bf16 MFMA, so the decode
+ *   kernel streams tiles with fully coalesced 16-byte loads.)  Token slots
+ *   that hold no valid token (headroom, alignment) are zero inside tiles
+ *   that hold at least one valid token; tiles without valid tokens are not
+ *   written.
+ *   PK_F32 layout: K as [Hkv][buf_tokens][d] floats, then V likewise.
+ *
+ * pk_workspace_bytes: bytes of the workspace that carries the plan's device
+ *   tables and the split-KV partial results for the given head shape.
+ */
+size_t pk_kv_buf_bytes(const pk_plan* plan, int Hkv, int d, int dtype);
+size_t pk_workspace_bytes(const pk_plan* plan, int Hq, int Hkv, int d, int dtype);
+
+/* Builds the device tables of the plan for this head shape and copies them
+ * into `workspace` (device, >= pk_workspace_bytes, 256-byte aligned) on
+ * `stream`.  Optional: the compute calls bind on first use of a
+ * (workspace, shape) pair; rebinding to another workspace is allowed.  The
+ * caller must not modify the workspace while the plan is in use. */
+int pk_plan_bind(pk_plan* plan, int Hq, int Hkv, int d, int dtype,
+                 void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
+ * pk_kv_reorganize -- Alg. 1 Part 2 / Sec. 3.2 "Contiguous Memory
+ * Consolidation": gathers the valid tokens of every request from the paged
+ * pool into the group buffers, each shared prefix once (taken through the
+ * block table of the family's lowest-index member in the group).
+ *
+ *   k_pages, v_pages  device [num_blocks][page_size][Hkv][d], dtype
+ *   block_table       device [n][max_blocks_per_req] int32, logical page b
+ *                     of request i -> physical block; entries beyond the
+ *                     request's length are ignored
+ *   num_blocks        physical blocks in the pool (for bounds validation of
+ *                     nothing but the caller's own sizes; block ids are
+ *                     clamped into [0, num_blocks))
+ *   kv_buf            device, pk_kv_buf_bytes; written
+ * Errors: PK_EINVAL (null pointer, page_size <= 0, max_blocks too small for
+ * the longest request), PK_EUNSUPPORTED (bf16 path needs d in {64, 128}).
+ */
+int pk_kv_reorganize(pk_plan* plan, const void* k_pages, const void* v_pages,
+                     const int32_t* block_table, int32_t max_blocks_per_req,
+                     int32_t page_size, int64_t num_blocks, int Hkv, int d, int dtype,
+                     void* kv_buf, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
+ * pk_packed_prefill_attn -- Sec. 3.1: attention computed directly over the
+ * union of valid query-key regions of each group: query tiles are cut from
+ * the group's packed token stream (a tile may span requests), only key tiles
+ * holding at least one unmasked pair are visited, block-diagonal causal mask,
+ * online softmax.  out[t,h,:] = softmax_j(scale * q[t,h].k[j,g(h)]) v[j,g(h)]
+ * over the keys j <= ctx + t of the same request, g(h) = h / (Hq/Hkv).
+ *
+ *   q    device [sum q_lens][Hq][d]    k, v  device [sum kv_lens][Hkv][d]
+ *   out  device [sum q_lens][Hq][d], out_dtype
+ * Errors: PK_EINVAL; PK_EUNSUPPORTED (bf16 path: d in {64,128}, Hq % Hkv == 0).
+ */
+int pk_packed_prefill_attn(pk_plan* plan, const void* q, const void* k, const void* v,
+                           void* out, float scale, int Hq, int Hkv, int d,
+                           int dtype, int out_dtype,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
+ * pk_packed_decode_attn -- Sec. 3.2: every request has ONE query row (the
+ * plan must have been made with q_lens == 1).  KV is read from the group
+ * buffer written by pk_kv_reorganize; a shared prefix segment is streamed
+ * once for all members of its (sub-)family in the group; segments are cut
+ * into fixed-size splits whose partial results are merged by log-sum-exp
+ * (the lossless merge of Sec. 1).
+ *
+ *   q    device [n][Hq][d]       kv_buf  device, as written by reorganize
+ *   out  device [n][Hq][d], out_dtype
+ * Errors: PK_EINVAL; PK_EUNSUPPORTED (bf16 path: d in {64,128}, Hq/Hkv in
+ * {1,2,4,8,16}).
+ */
+int pk_packed_decode_attn(pk_plan* plan, const void* q, const void* kv_buf,
+                          void* out, float scale, int Hq, int Hkv, int d,
+                          int dtype, int out_dtype,
+                          void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
+ * In-run comparison: per-request padded execution (Sec. 2.2: request-aligned
+ * tile grids, padding to the tile size, no cross-request packing).  Same
+ * mathematics and tensor conventions as the packed calls.
+ *   prefill: grid (request, query tile, head) sized by the longest request;
+ *            every request's last tile is padded; natural request order.
+ *   decode:  reads the PAGED pool through the block table, uniform number
+ *            of splits sized by the longest request, shared prefixes re-read
+ *            by every member.
+ */
+int pk_padded_prefill_attn(pk_plan* plan, const void* q, const void* k, const void* v,
+                           void* out, float scale, int Hq, int Hkv, int d,
+                           int dtype, int out_dtype,
+                           void* workspace, size_t workspace_bytes, void* stream);
+int pk_padded_decode_attn(pk_plan* plan, const void* q,
+                          const void* k_pages, const void* v_pages,
+                          const int32_t* block_table, int32_t max_blocks_per_req,
+                          int32_t page_size, int64_t num_blocks,
+                          void* out, float scale, int Hq, int Hkv, int d,
+                          int dtype, int out_dtype,
+                          void* workspace, size_t workspace_bytes, void* stream);
+
+/* Counts for the benchmark's work accounting (host):
+ *   what = 0: unmasked (query,key) pairs per head summed over requests
+ *   what = 1: (query,key) pairs issued to the MFMA units by the packed
+ *             prefill schedule, per head
+ *   what = 2: same for the padded prefill schedule
+ *   what = 3: decode work items of the bound shape; 4: partial slots
+ */
+int64_t pk_plan_stat(const pk_plan* plan, int what);
+
+/* Message of the last error on this thread ("" if none). */
+const char* pk_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PACKINFER_H */

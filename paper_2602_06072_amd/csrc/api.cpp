@@ -1,0 +1,213 @@
+// C ABI: argument validation, binding of plan tables to a workspace, launches.
+#include <hip/hip_runtime_api.h>
+
+#include <cstring>
+#include <string>
+
+#include "kernels.h"
+#include "plan.h"
+
+using namespace pk;
+
+namespace {
+
+int fail(int code, const std::string& msg) {
+    set_error(msg);
+    return code;
+}
+
+int hip_fail(const char* where, int err) {
+    return fail(PK_EHIP, std::string(where) + ": " + hipGetErrorString(static_cast<hipError_t>(err)));
+}
+
+bool shape_ok(int Hq, int Hkv, int d, int dtype, std::string& why) {
+    if (Hq <= 0 || Hkv <= 0 || d <= 0 || Hq % Hkv != 0) { why = "need Hq, Hkv, d > 0 and Hq % Hkv == 0"; return false; }
+    if (dtype != PK_BF16 && dtype != PK_F32) { why = "dtype must be PK_BF16 or PK_F32"; return false; }
+    return true;
+}
+
+// Makes sure the plan's device tables for this shape live in `workspace`.
+int ensure_bound(pk_plan* plan, int Hq, int Hkv, int d, int dtype, void* workspace,
+                 size_t workspace_bytes, void* stream) {
+    DeviceTables& t = plan->tables;
+    const bool same_shape = t.Hq == Hq && t.Hkv == Hkv && t.d == d && t.dtype == dtype;
+    if (same_shape && plan->bound_ws == workspace && plan->bound_bytes == workspace_bytes) return PK_OK;
+    if (!workspace) return fail(PK_EINVAL, "workspace is NULL");
+    if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0) return fail(PK_EINVAL, "workspace must be 256-byte aligned");
+    if (!same_shape) build_tables(*plan, Hq, Hkv, d, dtype, t);
+    if (workspace_bytes < t.total_bytes) return fail(PK_EINVAL, "workspace smaller than pk_workspace_bytes");
+    if (t.tables_bytes) {
+        hipError_t e = hipMemcpyAsync(workspace, t.host.data(), t.tables_bytes, hipMemcpyHostToDevice,
+                                      static_cast<hipStream_t>(stream));
+        if (e != hipSuccess) return hip_fail("pk_plan_bind (copy of tables)", e);
+    }
+    plan->bound_ws = workspace;
+    plan->bound_bytes = workspace_bytes;
+    return PK_OK;
+}
+
+const int32_t* tab(const pk_plan* plan, const TableRef& r) {
+    return reinterpret_cast<const int32_t*>(static_cast<const char*>(plan->bound_ws) + r.offset);
+}
+
+}  // namespace
+
+extern "C" size_t pk_kv_buf_bytes(const pk_plan* plan, int Hkv, int d, int dtype) {
+    if (!plan || Hkv <= 0 || d <= 0) return 0;
+    return kv_buf_bytes(*plan, Hkv, d, dtype);
+}
+
+extern "C" size_t pk_workspace_bytes(const pk_plan* plan, int Hq, int Hkv, int d, int dtype) {
+    std::string why;
+    if (!plan || !shape_ok(Hq, Hkv, d, dtype, why)) return 0;
+    const DeviceTables& t = plan->tables;
+    if (t.Hq == Hq && t.Hkv == Hkv && t.d == d && t.dtype == dtype) return t.total_bytes;
+    DeviceTables tmp;
+    build_tables(*plan, Hq, Hkv, d, dtype, tmp);
+    // keep the tables: the bind that follows reuses them
+    const_cast<pk_plan*>(plan)->tables = std::move(tmp);
+    const_cast<pk_plan*>(plan)->bound_ws = nullptr;
+    return plan->tables.total_bytes;
+}
+
+extern "C" int pk_plan_bind(pk_plan* plan, int Hq, int Hkv, int d, int dtype,
+                            void* workspace, size_t workspace_bytes, void* stream) {
+    std::string why;
+    if (!plan) return fail(PK_EINVAL, "pk_plan_bind: plan is NULL");
+    if (!shape_ok(Hq, Hkv, d, dtype, why)) return fail(PK_EINVAL, "pk_plan_bind: " + why);
+    plan->bound_ws = nullptr;                      // force the copy
+    return ensure_bound(plan, Hq, Hkv, d, dtype, workspace, workspace_bytes, stream);
+}
+
+extern "C" int pk_kv_reorganize(pk_plan* plan, const void* k_pages, const void* v_pages,
+                                const int32_t* block_table, int32_t max_blocks_per_req,
+                                int32_t page_size, int64_t num_blocks, int Hkv, int d, int dtype,
+                                void* kv_buf, void* workspace, size_t workspace_bytes, void* stream) {
+    std::string why;
+    if (!plan) return fail(PK_EINVAL, "pk_kv_reorganize: plan is NULL");
+    if (plan->n == 0) return PK_OK;
+    if (!k_pages || !v_pages || !block_table || !kv_buf) return fail(PK_EINVAL, "pk_kv_reorganize: NULL pointer");
+    if (page_size <= 0 || num_blocks <= 0) return fail(PK_EINVAL, "pk_kv_reorganize: page_size and num_blocks must be positive");
+    int Hq = plan->tables.Hkv == Hkv && plan->tables.d == d && plan->tables.dtype == dtype ? plan->tables.Hq : Hkv;
+    if (!shape_ok(Hq, Hkv, d, dtype, why)) return fail(PK_EINVAL, "pk_kv_reorganize: " + why);
+    if (dtype == PK_BF16 && d != 64 && d != 128) return fail(PK_EUNSUPPORTED, "pk_kv_reorganize: bf16 path needs d in {64,128}");
+    int32_t max_len = 0;
+    for (int32_t L : plan->kv_lens) max_len = L > max_len ? L : max_len;
+    if (static_cast<int64_t>(max_blocks_per_req) * page_size < max_len)
+        return fail(PK_EINVAL, "pk_kv_reorganize: max_blocks_per_req too small for the longest request");
+    int rc = ensure_bound(plan, Hq, Hkv, d, dtype, workspace, workspace_bytes, stream);
+    if (rc != PK_OK) return rc;
+    const DeviceTables& t = plan->tables;
+    ReorgArgs a{};
+    a.k_pages = k_pages; a.v_pages = v_pages; a.block_table = block_table;
+    a.max_blocks = max_blocks_per_req; a.page_size = page_size; a.num_blocks = num_blocks;
+    a.seg = tab(plan, t.reorg_seg); a.n_seg = t.n_reorg_seg; a.blk_first = tab(plan, t.reorg_blk_first);
+    a.kv_buf = kv_buf; a.buf_tokens = plan->buf_tokens; a.Hkv = Hkv; a.d = d;
+    const int e = dtype == PK_BF16 ? launch_reorg_bf16(a, stream) : launch_reorg_f32(a, stream);
+    return e ? hip_fail("pk_kv_reorganize", e) : PK_OK;
+}
+
+static int prefill_common(pk_plan* plan, const void* q, const void* k, const void* v, void* out,
+                          float scale, int Hq, int Hkv, int d, int dtype, int out_dtype,
+                          void* workspace, size_t workspace_bytes, void* stream, bool padded) {
+    const char* who = padded ? "pk_padded_prefill_attn" : "pk_packed_prefill_attn";
+    std::string why;
+    if (!plan) return fail(PK_EINVAL, std::string(who) + ": plan is NULL");
+    if (plan->n == 0) return PK_OK;
+    if (!q || !k || !v || !out) return fail(PK_EINVAL, std::string(who) + ": NULL pointer");
+    if (!shape_ok(Hq, Hkv, d, dtype, why)) return fail(PK_EINVAL, std::string(who) + ": " + why);
+    if (out_dtype != PK_BF16 && out_dtype != PK_F32) return fail(PK_EINVAL, std::string(who) + ": bad out_dtype");
+    if (dtype == PK_BF16 && d != 64 && d != 128) return fail(PK_EUNSUPPORTED, std::string(who) + ": bf16 path needs d in {64,128}");
+    if (dtype == PK_F32 && d > 256) return fail(PK_EUNSUPPORTED, std::string(who) + ": fp32 path needs d <= 256");
+    int rc = ensure_bound(plan, Hq, Hkv, d, dtype, workspace, workspace_bytes, stream);
+    if (rc != PK_OK) return rc;
+    const DeviceTables& t = plan->tables;
+    const DeviceTables::PrefillSched& s = padded ? t.padded : t.packed;
+    PrefillArgs a{};
+    a.q = q; a.k = k; a.v = v; a.out = out;
+    a.tiles = tab(plan, s.tiles); a.n_tiles = s.n_tiles;
+    a.row_q = tab(plan, s.row_q); a.row_lo = tab(plan, s.row_lo); a.row_hi = tab(plan, s.row_hi);
+    a.kvtiles = tab(plan, s.kvtiles);
+    a.q_start = tab(plan, t.q_start); a.kv_start = tab(plan, t.kv_start); a.n = plan->n;
+    int64_t tq = 0, tkv = 0;
+    for (int32_t i = 0; i < plan->n; ++i) { tq += plan->q_lens[i]; tkv += plan->kv_lens[i]; }
+    if (tkv > INT32_MAX) return fail(PK_EUNSUPPORTED, std::string(who) + ": more than 2^31 KV rows");
+    a.total_q_rows = tq; a.total_kv_rows = tkv;
+    a.Hq = Hq; a.Hkv = Hkv; a.d = d; a.scale = scale; a.out_f32 = out_dtype == PK_F32;
+    a.xcd_swizzle = padded ? 0 : 1;
+    const int e = dtype == PK_BF16 ? launch_prefill_bf16(a, stream) : launch_prefill_f32(a, stream);
+    return e ? hip_fail(who, e) : PK_OK;
+}
+
+extern "C" int pk_packed_prefill_attn(pk_plan* plan, const void* q, const void* k, const void* v,
+                                      void* out, float scale, int Hq, int Hkv, int d,
+                                      int dtype, int out_dtype,
+                                      void* workspace, size_t workspace_bytes, void* stream) {
+    return prefill_common(plan, q, k, v, out, scale, Hq, Hkv, d, dtype, out_dtype, workspace, workspace_bytes, stream, false);
+}
+
+extern "C" int pk_padded_prefill_attn(pk_plan* plan, const void* q, const void* k, const void* v,
+                                      void* out, float scale, int Hq, int Hkv, int d,
+                                      int dtype, int out_dtype,
+                                      void* workspace, size_t workspace_bytes, void* stream) {
+    return prefill_common(plan, q, k, v, out, scale, Hq, Hkv, d, dtype, out_dtype, workspace, workspace_bytes, stream, true);
+}
+
+extern "C" int pk_packed_decode_attn(pk_plan* plan, const void* q, const void* kv_buf,
+                                     void* out, float scale, int Hq, int Hkv, int d,
+                                     int dtype, int out_dtype,
+                                     void* workspace, size_t workspace_bytes, void* stream) {
+    std::string why;
+    if (!plan) return fail(PK_EINVAL, "pk_packed_decode_attn: plan is NULL");
+    if (plan->n == 0) return PK_OK;
+    if (!plan->decode_only) return fail(PK_EINVAL, "pk_packed_decode_attn: the plan must have q_len == 1 for every request");
+    if (!q || !kv_buf || !out) return fail(PK_EINVAL, "pk_packed_decode_attn: NULL pointer");
+    if (!shape_ok(Hq, Hkv, d, dtype, why)) return fail(PK_EINVAL, "pk_packed_decode_attn: " + why);
+    if (out_dtype != PK_BF16 && out_dtype != PK_F32) return fail(PK_EINVAL, "pk_packed_decode_attn: bad out_dtype");
+    if (dtype == PK_BF16 && (d != 64 && d != 128)) return fail(PK_EUNSUPPORTED, "pk_packed_decode_attn: bf16 path needs d in {64,128}");
+    if (dtype == PK_BF16 && Hq / Hkv > 32) return fail(PK_EUNSUPPORTED, "pk_packed_decode_attn: bf16 path needs Hq/Hkv <= 32");
+    if (dtype == PK_F32 && d > 256) return fail(PK_EUNSUPPORTED, "pk_packed_decode_attn: fp32 path needs d <= 256");
+    int rc = ensure_bound(plan, Hq, Hkv, d, dtype, workspace, workspace_bytes, stream);
+    if (rc != PK_OK) return rc;
+    const DeviceTables& t = plan->tables;
+    DecodeArgs a{};
+    a.q = q; a.kv_buf = kv_buf; a.out = out;
+    a.items = tab(plan, t.dec_items); a.n_items = t.n_dec_items; a.n_wide = t.n_dec_wide;
+    a.members = tab(plan, t.dec_members);
+    a.req_part_start = tab(plan, t.dec_req_part_start); a.req_parts = tab(plan, t.dec_req_parts);
+    a.req_seg = tab(plan, t.dec_req_seg);
+    a.part_o = reinterpret_cast<float*>(static_cast<char*>(workspace) + t.partial_offset);
+    a.part_lse = a.part_o + static_cast<size_t>(t.n_dec_parts) * Hq * d;
+    a.buf_tokens = plan->buf_tokens; a.n = plan->n;
+    a.Hq = Hq; a.Hkv = Hkv; a.d = d; a.scale = scale; a.out_f32 = out_dtype == PK_F32;
+    const int e = dtype == PK_BF16 ? launch_decode_bf16(a, stream) : launch_decode_f32(a, stream);
+    return e ? hip_fail("pk_packed_decode_attn", e) : PK_OK;
+}
+
+extern "C" int pk_padded_decode_attn(pk_plan* plan, const void* q,
+                                     const void* k_pages, const void* v_pages,
+                                     const int32_t* block_table, int32_t max_blocks_per_req,
+                                     int32_t page_size, int64_t num_blocks,
+                                     void* out, float scale, int Hq, int Hkv, int d,
+                                     int dtype, int out_dtype,
+                                     void* workspace, size_t workspace_bytes, void* stream) {
+    (void)plan; (void)q; (void)k_pages; (void)v_pages; (void)block_table; (void)max_blocks_per_req;
+    (void)page_size; (void)num_blocks; (void)out; (void)scale; (void)Hq; (void)Hkv; (void)d;
+    (void)dtype; (void)out_dtype; (void)workspace; (void)workspace_bytes; (void)stream;
+    return fail(PK_EUNSUPPORTED, "pk_padded_decode_attn: not built yet");
+}
+
+extern "C" int64_t pk_plan_stat(const pk_plan* plan, int what) {
+    if (!plan) return 0;
+    switch (what) {
+        case 0: return plan->unmasked_pairs;
+        case 1: return plan->tables.packed.issued_pairs;
+        case 2: return plan->tables.padded.issued_pairs;
+        case 3: return plan->tables.n_dec_items;
+        case 4: return plan->tables.n_dec_parts;
+        case 5: return plan->tables.dec_split_tokens;
+        case 6: return plan->tables.packed.n_tiles;
+        case 7: return plan->tables.padded.n_tiles;
+        default: return 0;
+    }
+}

@@ -1,0 +1,95 @@
+// Internal structures of the packing plan and of its device tables.
+// Host-side only; the device kernels see the tables as plain int32 arrays.
+#pragma once
+#include <cstddef>
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "../../include/packinfer.h"
+
+namespace pk {
+
+// ---- tile shapes shared by the schedule builder and the kernels -----------
+constexpr int kPrefillBM = 128;     // query rows per workgroup tile (4 waves x 32)
+constexpr int kPrefillBN = 64;      // keys per K/V tile
+constexpr int kDecodeBlock = PK_KV_BLOCK;   // tokens per buffer tile
+constexpr int kDecodeMaxRows = 32;  // query rows (members x heads-per-KV-head) per work item
+
+struct Member {                     // O_g[i] of Alg. 1 Part 2, offsets relative to the group base
+    int32_t req, prefix_off, lp, suffix_off, lq;
+};
+
+struct Group {
+    int64_t load = 0;               // L(S_g): unique KV tokens
+    int64_t buf_tokens = 0;         // M(S_g) incl. headroom
+    int64_t buf_base = 0;           // token offset of B_g inside the buffer
+    std::vector<Member> members;    // layout order
+};
+
+// One array inside the workspace.
+struct TableRef {
+    size_t offset = 0;              // bytes from the workspace base
+    size_t count = 0;               // int32 elements
+};
+
+// Host image of everything that is copied to the device for one head shape.
+struct DeviceTables {
+    int Hq = 0, Hkv = 0, d = 0, dtype = -1;
+    std::vector<int32_t> host;      // concatenated tables (each 64-int aligned)
+    // common
+    TableRef q_start, kv_start;     // [n+1] caller-order cumulative rows
+    // re-layout
+    TableRef reorg_seg;             // [nseg][4] dst0, ntok, req, src0 (sorted by dst0)
+    TableRef reorg_blk_first;       // [NB] first segment that may overlap tile b
+    int32_t n_reorg_seg = 0;
+    // decode
+    TableRef dec_items;             // [n_items][8]
+    TableRef dec_members;           // request ids of the work items' rows
+    TableRef dec_req_part_start;    // [n+1]
+    TableRef dec_req_parts;         // partial slot ids per request
+    TableRef dec_req_seg;           // [n][4] absolute prefix_off, L_P, suffix_off, L_Q
+    int32_t n_dec_items = 0, n_dec_wide = 0, n_dec_parts = 0, dec_split_tokens = 0;
+    // prefill (packed and padded schedules share one format)
+    struct PrefillSched {
+        TableRef tiles;             // [n_tiles][4] kv_first, n_kv, n_rows, reserved
+        TableRef row_q, row_lo, row_hi;   // [n_tiles*BM]
+        TableRef kvtiles;           // [n_kv_total][2] k_start, n | wavemask<<8 | full<<16
+        int32_t n_tiles = 0;
+        int64_t issued_pairs = 0;
+    } packed, padded;
+    // partial results (floats) live after the tables
+    size_t tables_bytes = 0;
+    size_t partial_offset = 0;      // bytes
+    size_t partial_bytes = 0;
+    size_t total_bytes = 0;
+};
+
+}  // namespace pk
+
+struct pk_plan {
+    int32_t n = 0;
+    int64_t token_budget = 0;
+    int32_t headroom = 0;
+    bool decode_only = false;       // every q_len == 1
+    std::vector<int32_t> kv_lens, q_lens, prefix_lens;   // prefix_lens: 0 if no family
+    std::vector<pk::Group> groups;
+    int64_t buf_tokens = 0;         // whole buffer, multiple of PK_KV_BLOCK
+    int64_t unique_tokens = 0;
+    int64_t unmasked_pairs = 0;
+    std::vector<int32_t> words;     // canonical serialisation
+    // binding state
+    pk::DeviceTables tables;
+    void* bound_ws = nullptr;
+    size_t bound_bytes = 0;
+};
+
+namespace pk {
+
+void set_error(const std::string& msg);
+
+// schedule.cpp
+void build_tables(const pk_plan& plan, int Hq, int Hkv, int d, int dtype, DeviceTables& out);
+size_t kv_buf_bytes(const pk_plan& plan, int Hkv, int d, int dtype);
+
+}  // namespace pk

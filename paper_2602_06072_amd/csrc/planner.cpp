@@ -1,0 +1,213 @@
+// Packing planner: Alg. 1 Part 1 (greedy length-balanced grouping under the
+// token term of the feasibility test, Eq. 2) and the bookkeeping of Part 2
+// (prefix-first layout, offset tables O_g).  Host only, integers only,
+// deterministic: the same inputs always give the same serialised words.
+#include <algorithm>
+#include <map>
+#include <new>
+#include <numeric>
+
+#include "plan.h"
+
+namespace pk {
+
+static thread_local std::string g_error;
+void set_error(const std::string& msg) { g_error = msg; }
+
+namespace {
+
+struct Item {                       // atomic unit of assignment: a request or a (sub-)family
+    int64_t length;                 // unique tokens: L_P + sum of suffixes (Sec. 3.2)
+    int32_t first;                  // lowest member index (tie-break)
+    int32_t lp;
+    std::vector<int32_t> members;   // ascending request index
+};
+
+inline void push64(std::vector<int32_t>& w, int64_t x) {
+    w.push_back(static_cast<int32_t>(static_cast<uint32_t>(x & 0xFFFFFFFFll)));
+    w.push_back(static_cast<int32_t>(static_cast<uint32_t>((x >> 32) & 0xFFFFFFFFll)));
+}
+
+int fail(const char* msg) {
+    set_error(msg);
+    return PK_EINVAL;
+}
+
+}  // namespace
+}  // namespace pk
+
+using namespace pk;
+
+extern "C" int pk_pack_plan(const int32_t* kv_lens, const int32_t* q_lens,
+                            const int32_t* prefix_ids, const int32_t* prefix_lens,
+                            int32_t n, int64_t token_budget, int32_t headroom, pk_plan** out) {
+    if (!out) return fail("pk_pack_plan: out is NULL");
+    *out = nullptr;
+    if (n < 0) return fail("pk_pack_plan: n < 0");
+    if (n > 0 && !kv_lens) return fail("pk_pack_plan: kv_lens is NULL");
+    if (token_budget <= 0) return fail("pk_pack_plan: token_budget must be positive");
+    if (headroom < 0) return fail("pk_pack_plan: headroom must be non-negative");
+    if ((prefix_ids == nullptr) != (prefix_lens == nullptr))
+        return fail("pk_pack_plan: prefix_ids and prefix_lens must be given together");
+
+    std::map<int32_t, int32_t> fam_len;
+    for (int32_t i = 0; i < n; ++i) {
+        if (kv_lens[i] <= 0) return fail("pk_pack_plan: kv_len must be positive");
+        if (q_lens && (q_lens[i] <= 0 || q_lens[i] > kv_lens[i]))
+            return fail("pk_pack_plan: q_len must be in [1, kv_len]");
+        if (prefix_ids) {
+            const int32_t pl = prefix_lens[i];
+            if (pl < 0 || pl > kv_lens[i]) return fail("pk_pack_plan: prefix_len must be in [0, kv_len]");
+            if (prefix_ids[i] >= 0 && pl > 0) {
+                auto it = fam_len.emplace(prefix_ids[i], pl).first;
+                if (it->second != pl) return fail("pk_pack_plan: prefix_len differs inside a family");
+            }
+        }
+    }
+
+    pk_plan* plan = new (std::nothrow) pk_plan();
+    if (!plan) { set_error("pk_pack_plan: out of host memory"); return PK_ENOMEM; }
+    plan->n = n;
+    plan->token_budget = token_budget;
+    plan->headroom = headroom;
+    plan->kv_lens.assign(kv_lens, kv_lens + n);
+    if (q_lens) plan->q_lens.assign(q_lens, q_lens + n); else plan->q_lens = plan->kv_lens;
+    plan->prefix_lens.assign(n, 0);
+    plan->decode_only = n > 0;
+    for (int32_t i = 0; i < n; ++i) {
+        if (plan->q_lens[i] != 1) plan->decode_only = false;
+        const int64_t lq = plan->q_lens[i], ctx = plan->kv_lens[i] - lq;
+        plan->unmasked_pairs += lq * ctx + lq * (lq + 1) / 2;
+    }
+
+    // ---- items -------------------------------------------------------------
+    const int64_t C = token_budget;
+    std::vector<Item> items;
+    std::map<int32_t, std::vector<int32_t>> families;   // ordered by id; order is irrelevant after the sort
+    for (int32_t i = 0; i < n; ++i) {
+        const bool in_family = prefix_ids && prefix_ids[i] >= 0 && prefix_lens[i] > 0;
+        if (in_family) {
+            families[prefix_ids[i]].push_back(i);
+            plan->prefix_lens[i] = prefix_lens[i];
+        } else {
+            items.push_back(Item{kv_lens[i], i, 0, {i}});
+        }
+    }
+    for (auto& kv : families) {
+        const std::vector<int32_t>& mem = kv.second;
+        const int32_t lp = prefix_lens[mem[0]];
+        Item cur{lp, mem[0], lp, {}};
+        for (int32_t i : mem) {
+            const int64_t lq = kv_lens[i] - lp;
+            if (!cur.members.empty() && cur.length + lq > C) {     // cut: fewest consecutive sub-families
+                items.push_back(cur);
+                cur = Item{lp, i, lp, {}};
+            }
+            if (cur.members.empty()) cur.first = i;
+            cur.members.push_back(i);
+            cur.length += lq;
+        }
+        items.push_back(cur);
+    }
+
+    // ---- Part 1: greedy least-loaded assignment ------------------------------
+    int64_t l_total = 0;
+    for (const Item& it : items) l_total += it.length;
+    const int64_t G0 = (l_total + C - 1) / C;
+    std::vector<int64_t> loads(static_cast<size_t>(G0), 0);
+    std::vector<std::vector<int32_t>> assigned(static_cast<size_t>(G0));   // item indices
+    std::vector<int32_t> order(items.size());
+    std::iota(order.begin(), order.end(), 0);
+    std::sort(order.begin(), order.end(), [&](int32_t a, int32_t b) {
+        if (items[a].length != items[b].length) return items[a].length > items[b].length;
+        return items[a].first < items[b].first;
+    });
+    for (int32_t idx : order) {
+        const Item& it = items[idx];
+        size_t g = 0;
+        bool have = !loads.empty();
+        for (size_t j = 1; j < loads.size(); ++j)
+            if (loads[j] < loads[g]) g = j;                       // lowest index on ties
+        if (have && loads[g] + it.length <= C) {
+            loads[g] += it.length;
+            assigned[g].push_back(idx);
+        } else {                                                  // else-branch: open a new group
+            loads.push_back(it.length);
+            assigned.push_back({idx});
+        }
+    }
+
+    // ---- Part 2: prefix-first layout, offset tables --------------------------
+    int64_t base = 0;
+    for (size_t g = 0; g < loads.size(); ++g) {
+        if (assigned[g].empty()) continue;
+        Group grp;
+        grp.load = loads[g];
+        int64_t delta = 0;
+        for (int32_t idx : assigned[g]) {
+            const Item& it = items[idx];
+            const int64_t poff = delta;
+            delta += it.lp;
+            for (int32_t i : it.members) {
+                const int32_t lq = kv_lens[i] - it.lp;
+                grp.members.push_back(Member{i, static_cast<int32_t>(poff), it.lp,
+                                             static_cast<int32_t>(delta), lq});
+                delta += lq + headroom;
+            }
+        }
+        if (delta > INT32_MAX) { delete plan; return fail("pk_pack_plan: group buffer exceeds 2^31 tokens"); }
+        grp.buf_tokens = delta;
+        grp.buf_base = base;
+        base = (base + delta + PK_GROUP_ALIGN - 1) / PK_GROUP_ALIGN * PK_GROUP_ALIGN;
+        plan->unique_tokens += grp.load;
+        plan->groups.push_back(std::move(grp));
+    }
+    plan->buf_tokens = base;
+    if (base > INT32_MAX) { delete plan; return fail("pk_pack_plan: buffer exceeds 2^31 tokens"); }
+
+    // ---- canonical serialisation ---------------------------------------------
+    std::vector<int32_t>& w = plan->words;
+    w.push_back(0x504B504C);
+    w.push_back(1);
+    w.push_back(n);
+    w.push_back(static_cast<int32_t>(plan->groups.size()));
+    push64(w, C);
+    w.push_back(headroom);
+    w.push_back(PK_GROUP_ALIGN);
+    push64(w, plan->buf_tokens);
+    for (const Group& grp : plan->groups) {
+        push64(w, grp.load);
+        push64(w, grp.buf_tokens);
+        push64(w, grp.buf_base);
+        w.push_back(static_cast<int32_t>(grp.members.size()));
+        for (const Member& m : grp.members) {
+            w.push_back(m.req); w.push_back(m.prefix_off); w.push_back(m.lp);
+            w.push_back(m.suffix_off); w.push_back(m.lq);
+        }
+    }
+    *out = plan;
+    return PK_OK;
+}
+
+extern "C" void pk_plan_destroy(pk_plan* plan) { delete plan; }
+
+extern "C" int32_t pk_plan_num_requests(const pk_plan* plan) { return plan ? plan->n : 0; }
+extern "C" int32_t pk_plan_num_groups(const pk_plan* plan) {
+    return plan ? static_cast<int32_t>(plan->groups.size()) : 0;
+}
+extern "C" int64_t pk_plan_buf_tokens(const pk_plan* plan) { return plan ? plan->buf_tokens : 0; }
+extern "C" int64_t pk_plan_unique_tokens(const pk_plan* plan) { return plan ? plan->unique_tokens : 0; }
+
+extern "C" int64_t pk_plan_serialized_words(const pk_plan* plan) {
+    return plan ? static_cast<int64_t>(plan->words.size()) : 0;
+}
+
+extern "C" int64_t pk_plan_serialize(const pk_plan* plan, int32_t* out, int64_t cap) {
+    if (!plan || !out) return fail("pk_plan_serialize: NULL argument");
+    const int64_t nw = static_cast<int64_t>(plan->words.size());
+    if (cap < nw) return fail("pk_plan_serialize: capacity too small");
+    std::copy(plan->words.begin(), plan->words.end(), out);
+    return nw;
+}
+
+extern "C" const char* pk_last_error(void) { return pk::g_error.c_str(); }

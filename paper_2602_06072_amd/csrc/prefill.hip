@@ -1,0 +1,264 @@
+// Packed prefill attention, bf16 MFMA (Sec. 3.1): causal attention over the
+// packed query-key regions of each group with a per-request block-diagonal
+// mask and online softmax.  The same kernel runs the padded per-request
+// schedule of the in-run comparison; only the tables differ.
+//
+// Workgroup = (query tile of 128 packed rows, query head), 4 waves x 32 rows.
+// Per key tile of 64 keys a wave computes
+//     S^T (keys x queries) = K . Q^T      A = K rows from LDS, B = Q in registers
+//     O^T (d x queries)   += V^T . P^T    A = V^T by LDS transpose reads, B = P
+// with v_mfma_f32_32x32x16_bf16.  Working on the transposed problem keeps each
+// query's scores inside one lane (plus its partner lane^32), so the softmax
+// row reductions are in-register, and P^T leaves the first MFMA already in the
+// operand layout of the second.  K/V tiles are staged through LDS (double
+// buffered, one barrier per tile); global loads of tile j+1 are issued before
+// the math of tile j.  MFMA-bound: 4*D flops per (query, key) pair.
+#include "common.hip.h"
+#include "kernels.h"
+
+namespace pk {
+namespace {
+
+constexpr int BM = 128, BN = 64;
+
+template <int D> struct Smem {
+    static constexpr int KP = D * 2 + 16;          // K row pitch (bytes): conflict-free 16-byte row reads
+    static constexpr int VP = D * 2 + 64;          // V row pitch (bytes): transpose reads of 8 rows hit 8 x 16 banks
+    static constexpr int K_BYTES = BN * KP;
+    static constexpr int V_BYTES = BN * VP;
+    static constexpr int STAGE = K_BYTES + V_BYTES;
+    static constexpr int TOTAL = 2 * STAGE;
+};
+
+typedef bf16x4 __attribute__((address_space(3))) * lds_bf16x4_ptr;
+
+template <int D>
+__global__ __launch_bounds__(256, 2) void prefill_bf16_kernel(PrefillArgs a) {
+    using SM = Smem<D>;
+    constexpr int KS = D / 16;                     // MFMA k-steps over the head dimension
+    constexpr int DB = D / 32;                     // 32-column blocks of the output
+    constexpr int CH = D / 8;                      // 16-byte chunks per row
+    constexpr int LD = BN * CH / 256;              // chunks per thread per tile (K and V each)
+    extern __shared__ __align__(16) unsigned char smem[];
+
+    // ---- work unit ---------------------------------------------------------
+    const int r = a.Hq / a.Hkv;
+    int tile, head, kvh;
+    if (a.xcd_swizzle) {
+        // consecutive workgroup ids go round-robin over the 8 XCDs: keep the r heads of one
+        // (tile, KV head) pair on one XCD and adjacent in time so K/V tiles hit in its L2
+        const int x = blockIdx.x, c = x & 7, y = x >> 3, j = y % r, slot = y / r;
+        const int64_t p = static_cast<int64_t>(slot) * 8 + c;
+        if (p >= static_cast<int64_t>(a.n_tiles) * a.Hkv) return;
+        tile = static_cast<int>(p / a.Hkv); kvh = static_cast<int>(p % a.Hkv); head = kvh * r + j;
+    } else {
+        tile = blockIdx.x / a.Hq; head = blockIdx.x % a.Hq; kvh = head / r;
+    }
+    const int32_t* desc = a.tiles + 4 * static_cast<int64_t>(tile);
+    const int kv_first = desc[0], n_kv = desc[1];
+    if (n_kv == 0) return;
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 31, hlf = lane >> 5;
+    const int rr = tile * BM + wave * 32 + n;
+    const int qrow = a.row_q[rr], lo = a.row_lo[rr], hi = a.row_hi[rr];
+
+    // ---- Q operand: lane (n, hlf) holds Q[row n][16s + 8hlf .. +8] ----------
+    bf16x8 qf[KS];
+    {
+        const uint16_t* qp = static_cast<const uint16_t*>(a.q) +
+                             (static_cast<int64_t>(qrow < 0 ? 0 : qrow) * a.Hq + head) * D + 8 * hlf;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            uint4 raw = make_uint4(0, 0, 0, 0);
+            if (qrow >= 0) raw = *reinterpret_cast<const uint4*>(qp + 16 * s);
+            qf[s] = __builtin_bit_cast(bf16x8, raw);
+        }
+    }
+
+    floatx16 o[DB];
+#pragma unroll
+    for (int b = 0; b < DB; ++b)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) o[b][e] = 0.f;
+    float m = -INFINITY, l = 0.f;
+    const float sl2 = a.scale * kLog2e;
+
+    // ---- tile loader -------------------------------------------------------
+    const uint4* kg = static_cast<const uint4*>(a.k);
+    const uint4* vg = static_cast<const uint4*>(a.v);
+    uint4 kreg[LD], vreg[LD];
+    auto gload = [&](int j) {
+        const int k_start = a.kvtiles[2 * static_cast<int64_t>(kv_first + j)];
+#pragma unroll
+        for (int i = 0; i < LD; ++i) {
+            const int idx = tid + 256 * i, row = idx / CH, c = idx % CH;
+            int64_t kr = static_cast<int64_t>(k_start) + row;
+            kr = kr < a.total_kv_rows ? kr : a.total_kv_rows - 1;
+            const int64_t off = (kr * a.Hkv + kvh) * CH + c;
+            kreg[i] = kg[off];
+            vreg[i] = vg[off];
+        }
+    };
+    auto sstore = [&](int stage) {
+        unsigned char* ks = smem + stage * SM::STAGE;
+        unsigned char* vs = ks + SM::K_BYTES;
+#pragma unroll
+        for (int i = 0; i < LD; ++i) {
+            const int idx = tid + 256 * i, row = idx / CH, c = idx % CH;
+            *reinterpret_cast<uint4*>(ks + row * SM::KP + c * 16) = kreg[i];
+            *reinterpret_cast<uint4*>(vs + row * SM::VP + c * 16) = vreg[i];
+        }
+    };
+
+    gload(0);
+    sstore(0);
+    __syncthreads();
+
+    for (int j = 0; j < n_kv; ++j) {
+        const int stage = j & 1;
+        if (j + 1 < n_kv) gload(j + 1);
+        const int32_t k_start = a.kvtiles[2 * static_cast<int64_t>(kv_first + j)];
+        const int32_t info = a.kvtiles[2 * static_cast<int64_t>(kv_first + j) + 1];
+        const int code = (info >> (8 + 2 * wave)) & 3;       // 0 skip, 1 masked, 2 unmasked
+        if (code != 0) {
+            const unsigned char* ks = smem + stage * SM::STAGE;
+            const unsigned char* vs = ks + SM::K_BYTES;
+            // ---- S^T = K . Q^T: two blocks of 32 keys -----------------------
+            floatx16 s[2];
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) s[kb][e] = 0.f;
+                const unsigned char* krow = ks + (32 * kb + n) * SM::KP + 16 * hlf;
+#pragma unroll
+                for (int st = 0; st < KS; ++st) {
+                    const bf16x8 kf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(krow + 32 * st));
+                    s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[st], s[kb], 0, 0, 0);
+                }
+            }
+            // lane (n, hlf), register e of block kb: key k_start + 32kb + 8(e/4) + 4hlf + e%4
+            float mx = -INFINITY;
+            if (code == 1) {
+                // keys past the tile's valid count belong to whatever follows in memory
+                const int hi_t = min(hi, k_start + (info & 0xFF));
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        const int key = k_start + 32 * kb + 8 * (e >> 2) + 4 * hlf + (e & 3);
+                        const float x = (key >= lo && key < hi_t) ? s[kb][e] * sl2 : -INFINITY;
+                        s[kb][e] = x;
+                        mx = fmaxf(mx, x);
+                    }
+            } else {
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        const float x = s[kb][e] * sl2;
+                        s[kb][e] = x;
+                        mx = fmaxf(mx, x);
+                    }
+            }
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            const float m_new = fmaxf(m, mx);
+            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+            const float alpha = exp2f(m - m_use);
+            m = m_new;
+            float ps = 0.f;
+            bf16x8 pf[2][2];
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
+                float p[16];
+#pragma unroll
+                for (int e = 0; e < 16; ++e) { p[e] = exp2f(s[kb][e] - m_use); ps += p[e]; }
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    uint4 w;
+                    w.x = pack_bf16x2(p[8 * t + 0], p[8 * t + 1]); w.y = pack_bf16x2(p[8 * t + 2], p[8 * t + 3]);
+                    w.z = pack_bf16x2(p[8 * t + 4], p[8 * t + 5]); w.w = pack_bf16x2(p[8 * t + 6], p[8 * t + 7]);
+                    pf[kb][t] = __builtin_bit_cast(bf16x8, w);
+                }
+            }
+            l = l * alpha + ps;
+#pragma unroll
+            for (int b = 0; b < DB; ++b)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) o[b][e] *= alpha;
+            // ---- O^T += V^T . P^T --------------------------------------------
+            // MFMA (kb, t) contracts keys 32kb + 16t + {4hlf..4hlf+3} and {8+4hlf..8+4hlf+3}; the
+            // transpose read hands lane i of a 16-lane group column i of a 4-row x 16-column patch.
+            const int i16 = lane & 15, gl = (lane >> 4) & 1;
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    const int key0 = 32 * kb + 16 * t + 4 * hlf + (i16 >> 2);
+#pragma unroll
+                    for (int b = 0; b < DB; ++b) {
+                        const int col = 32 * b + 16 * gl + 4 * (i16 & 3);
+                        const unsigned char* p0 = vs + key0 * SM::VP + col * 2;
+                        const bf16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)(p0));
+                        const bf16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)(p0 + 8 * SM::VP));
+                        const bf16x8 vf = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
+                        o[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[kb][t], o[b], 0, 0, 0);
+                    }
+                }
+        }
+        if (j + 1 < n_kv) sstore(stage ^ 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue ----------------------------------------------------------
+    l += __shfl_xor(l, 32, 64);
+    if (qrow < 0) return;
+    const float inv = l > 0.f ? 1.f / l : 0.f;
+    const int64_t obase = (static_cast<int64_t>(qrow) * a.Hq + head) * D;
+#pragma unroll
+    for (int b = 0; b < DB; ++b)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+            const int col = 32 * b + 8 * q4 + 4 * hlf;
+            const float x0 = o[b][4 * q4] * inv, x1 = o[b][4 * q4 + 1] * inv;
+            const float x2 = o[b][4 * q4 + 2] * inv, x3 = o[b][4 * q4 + 3] * inv;
+            if (a.out_f32) {
+                *reinterpret_cast<float4*>(static_cast<float*>(a.out) + obase + col) = make_float4(x0, x1, x2, x3);
+            } else {
+                *reinterpret_cast<uint2*>(static_cast<uint16_t*>(a.out) + obase + col) =
+                    make_uint2(pack_bf16x2(x0, x1), pack_bf16x2(x2, x3));
+            }
+        }
+}
+
+template <int D>
+int launch_p(const PrefillArgs& a, hipStream_t st) {
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(prefill_bf16_kernel<D>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, Smem<D>::TOTAL);
+        if (e != hipSuccess) return static_cast<int>(e);
+        attr_set = true;
+    }
+    const int r = a.Hq / a.Hkv;
+    int64_t grid;
+    if (a.xcd_swizzle) {
+        const int64_t pairs = static_cast<int64_t>(a.n_tiles) * a.Hkv;
+        grid = (pairs + 7) / 8 * 8 * r;
+    } else {
+        grid = static_cast<int64_t>(a.n_tiles) * a.Hq;
+    }
+    if (grid == 0) return 0;
+    hipLaunchKernelGGL(prefill_bf16_kernel<D>, dim3(static_cast<unsigned>(grid)), dim3(256), Smem<D>::TOTAL, st, a);
+    return static_cast<int>(hipGetLastError());
+}
+
+}  // namespace
+
+int launch_prefill_bf16(const PrefillArgs& a, void* stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (a.d == 128) return launch_p<128>(a, st);
+    if (a.d == 64) return launch_p<64>(a, st);
+    return static_cast<int>(hipErrorInvalidValue);
+}
+
+}  // namespace pk

@@ -1,0 +1,142 @@
+"""Host-side checks of the C-ABI library (no GPU compute): it loads, exports
+every symbol the header declares, its planner reproduces the oracle planner
+bit for bit, and its error paths return codes instead of crashing."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+from hypothesis import given, settings, strategies as st
+
+from oracle import planner as opl
+from paper_2602_06072_amd import binding as pk
+from paper_2602_06072_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_exports_match_header():
+    text = open(os.path.join(ROOT, "include", "packinfer.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = sorted(set(re.findall(r"\b(pk_[a-z0-9_]+)\s*\(", text)))
+    assert declared == sorted(pk.EXPORTS)
+    L = pk.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def oracle_words(kv, ql, pid, plen, C, hr):
+    return np.array(opl.make_plan(kv, ql, pid, plen, C, hr).words(), dtype=np.int32)
+
+
+@st.composite
+def plan_inputs(draw):
+    n = draw(st.integers(0, 40))
+    C = draw(st.integers(4, 300))
+    hr = draw(st.integers(0, 3))
+    if not draw(st.booleans()):
+        return [draw(st.integers(1, 150)) for _ in range(n)], None, None, C, hr
+    nf = draw(st.integers(1, 5))
+    fl = [draw(st.integers(0, 80)) for _ in range(nf)]
+    pid = [draw(st.integers(-1, nf - 1)) for _ in range(n)]
+    plen = [0 if p < 0 else fl[p] for p in pid]
+    kv = [plen[i] + draw(st.integers(0 if plen[i] else 1, 60)) for i in range(n)]
+    return kv, pid, plen, C, hr
+
+
+@settings(max_examples=400, deadline=None)
+@given(plan_inputs())
+def test_plan_is_bit_exact_with_oracle(inp):
+    kv, pid, plen, C, hr = inp
+    plan = pk.pack_plan(kv, None, pid, plen, C, hr)
+    assert np.array_equal(plan.words(), oracle_words(kv, None, pid, plen, C, hr))
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_plan_bit_exact_on_benchmark_configs(seed):
+    cases = []
+    l2 = wl.config2_lengths(seed)
+    cases.append((l2, None, None, None, 16384))
+    l3 = wl.config3_lengths(seed)
+    cases.append((l3, np.ones_like(l3), None, None, 16384))
+    kv4, pid4, pl4 = wl.config4_structure(seed)
+    cases.append((kv4, np.ones_like(kv4), pid4, pl4, 16384))
+    chunk, ctx, dec = wl.config5_structure(seed)
+    cases.append((chunk + ctx, chunk, None, None, 16384))
+    cases.append((dec, np.ones_like(dec), None, None, 16384))
+    rng = np.random.default_rng(seed)
+    l1 = rng.integers(16, 513, size=8)
+    cases.append((l1, None, None, None, 1024))
+    for kv, ql, pid, plen, C in cases:
+        a = pk.pack_plan(kv, ql, pid, plen, C)
+        b = pk.pack_plan(kv, ql, pid, plen, C)
+        want = oracle_words([int(x) for x in kv], None if ql is None else [int(x) for x in ql],
+                            None if pid is None else [int(x) for x in pid],
+                            None if plen is None else [int(x) for x in plen], C, 0)
+        assert np.array_equal(a.words(), want)
+        assert np.array_equal(a.words(), b.words())           # reproducible
+        assert a.unique_tokens == sum(g["load"] for g in a.groups())
+
+
+def test_config4_families_are_colocated_and_prefix_counted_once():
+    kv, pid, plen = wl.config4_structure(0)
+    plan = pk.pack_plan(kv, np.ones_like(kv), pid, plen, 16384)
+    where = {}
+    for gi, g in enumerate(plan.groups()):
+        for (req, poff, lp, soff, lq) in g["members"]:
+            where.setdefault(int(pid[req]), set()).add((gi, poff))
+    assert all(len(v) == 1 for v in where.values())
+    uniq = sum(int(plen[np.where(pid == f)[0][0]]) for f in set(pid.tolist())) + int((kv - plen).sum())
+    assert plan.unique_tokens == uniq
+    assert uniq < int(kv.sum()) / 4                           # prefix sharing removes most of the volume
+
+
+def test_error_paths_return_codes():
+    L = pk.lib()
+    bad = [
+        dict(kv_lens=[0, 3]), dict(kv_lens=[3], q_lens=[4]), dict(kv_lens=[3], q_lens=[0]),
+        dict(kv_lens=[3], token_budget=0), dict(kv_lens=[3], headroom=-1),
+        dict(kv_lens=[5, 5], prefix_ids=[0, 0], prefix_lens=[2, 3]),
+        dict(kv_lens=[5], prefix_ids=[0], prefix_lens=[6]),
+        dict(kv_lens=[5], prefix_ids=[0], prefix_lens=[-1]),
+        dict(kv_lens=[5], prefix_ids=[0]),
+    ]
+    for kw in bad:
+        kw.setdefault("token_budget", 8)
+        with pytest.raises(pk.PackInferError):
+            pk.pack_plan(**kw)
+        assert L.pk_last_error() != b""
+    empty = pk.pack_plan([], token_budget=8)
+    assert empty.num_groups == 0 and empty.buf_tokens == 0
+    # NULL out pointer / NULL plan are reported, not dereferenced
+    assert L.pk_pack_plan(None, None, None, None, 0, 8, 0, None) == -1
+    assert L.pk_plan_num_groups(None) == 0
+    assert L.pk_plan_serialize(None, None, 0) == -1
+    plan = pk.pack_plan([4, 4], [1, 1], token_budget=8)
+    small = np.zeros(3, dtype=np.int32)
+    assert L.pk_plan_serialize(plan.handle, small.ctypes.data, 3) == -1
+    # compute entry points validate before touching the device
+    assert L.pk_packed_decode_attn(plan.handle, None, None, None, 1.0, 4, 2, 64, 0, 0, None, 0, None) == -1
+    assert L.pk_packed_prefill_attn(plan.handle, None, None, None, None, 1.0, 4, 2, 64, 0, 0, None, 0, None) == -1
+    assert L.pk_packed_prefill_attn(None, None, None, None, None, 1.0, 4, 2, 64, 0, 0, None, 0, None) == -1
+    assert L.pk_kv_reorganize(plan.handle, None, None, None, 1, 16, 1, 2, 64, 0, None, None, 0, None) == -1
+    prefill_plan = pk.pack_plan([4, 4], token_budget=8)
+    dummy = ctypes.create_string_buffer(16)
+    p = ctypes.addressof(dummy)
+    assert L.pk_packed_decode_attn(prefill_plan.handle, p, p, p, 1.0, 4, 2, 64, 0, 0, p, 16, None) == -1   # not a decode plan
+    assert L.pk_packed_prefill_attn(plan.handle, p, p, p, p, 1.0, 4, 3, 64, 0, 0, p, 16, None) == -1        # Hq % Hkv
+    assert L.pk_packed_prefill_attn(plan.handle, p, p, p, p, 1.0, 4, 2, 80, 0, 0, p, 16, None) == -3        # d unsupported (bf16)
+
+
+def test_sizes_and_stats():
+    lens = wl.config2_lengths(0)
+    plan = pk.pack_plan(lens, token_budget=16384)
+    ws = plan.workspace_bytes(32, 8, 128, pk.PK_BF16)
+    assert ws > 0 and ws % 256 == 0
+    L = lens.astype(np.int64)
+    assert plan.stat(0) == int((L * (L + 1) // 2).sum())
+    assert plan.stat(1) >= plan.stat(0)                       # issued pairs cover the unmasked ones
+    assert plan.stat(2) >= plan.stat(1)                       # padding never issues less than packing
+    assert plan.buf_tokens % pk.PK_KV_BLOCK == 0
+    assert plan.kv_buf_bytes(8, 128, pk.PK_BF16) == plan.buf_tokens * 8 * 128 * 2 * 2
