@@ -1,0 +1,258 @@
+#!/usr/bin/env python3
+"""Benchmark of the packed-attention hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--seed S] [--no-extras]
+
+Prints ONE JSON line.  Headline workload: the Llama-3-8B-shaped prefill
+attention layer (64 requests, lognormal lengths, 32 query / 8 KV heads,
+head_dim 128, bf16, causal, token budget 16384).  A step is one pass of the
+hot path over that batch: pack_plan on the host, the copy of the plan's
+integer tables to the device, and the packed prefill kernel.  Inputs are
+resident in HBM before the timed region starts.
+
+  value     whole-step throughput in TFLOP/s: algorithmic flops
+            (4 * d * Hq * unmasked pairs) / wall time of the timed steps
+  roofline  packed prefill kernel alone (HIP events on the launch stream),
+            against the dense bf16 MFMA peak
+  cpu_baseline  the CPU oracle timed on a bounded sample of the same batch
+  extra     the in-run padded baseline, planner time, and the decode /
+            re-layout / shared-prefix / mixed-step workloads with their own
+            HBM roofline fractions
+
+More than one GPU is not supported: this path has no sharding or collectives.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+HBM_PEAK_GBS = 8000.0
+
+
+def _events(n):
+    import torch
+    return [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+
+
+def _time_launches(fn, iters, warmup=3):
+    """Average duration (ms) of fn's device work, one event pair per launch."""
+    import torch
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    ev = _events(iters)
+    for a, b in ev:
+        a.record()
+        fn()
+        b.record()
+    torch.cuda.synchronize()
+    t = [a.elapsed_time(b) for a, b in ev]
+    return float(np.mean(t)), float(np.min(t))
+
+
+def prefill_flops(w, pairs):
+    return 4.0 * w.d * w.Hq * pairs
+
+
+def bench_prefill(w, steps, warmup, with_padded=True):
+    import torch
+    from paper_2602_06072_amd import binding as pk
+    res = {}
+    out = torch.empty(w.q.shape, dtype=torch.bfloat16, device=w.q.device)
+    plan0 = pk.pack_plan(w.kv_lens, w.q_lens, token_budget=w.token_budget)
+    ws = pk.new_workspace(plan0, w.Hq, w.Hkv, w.d, pk.PK_BF16)
+    pairs = plan0.stat(0)
+    flops = prefill_flops(w, pairs)
+
+    def step():
+        plan = pk.pack_plan(w.kv_lens, w.q_lens, token_budget=w.token_budget)
+        pk.plan_bind(plan, w.Hq, w.Hkv, w.d, pk.PK_BF16, ws)
+        pk.packed_prefill_attn(plan, w.q, w.k, w.v, out, w.scale, ws)
+        return plan
+
+    keep = [step() for _ in range(warmup)]          # plans stay alive until their copies have run
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    keep = [step() for _ in range(steps)]
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    del keep
+    res["ms_per_step"] = wall / steps * 1e3
+    res["step_tflops"] = flops * steps / wall / 1e12
+
+    # kernel alone
+    pk.plan_bind(plan0, w.Hq, w.Hkv, w.d, pk.PK_BF16, ws)
+    avg, mn = _time_launches(lambda: pk.packed_prefill_attn(plan0, w.q, w.k, w.v, out, w.scale, ws), max(steps, 10))
+    res["kernel_ms"] = avg
+    res["kernel_ms_min"] = mn
+    res["kernel_tflops"] = flops / (avg * 1e-3) / 1e12
+    res["flops"] = flops
+    res["pairs"] = pairs
+    res["issued_pairs_packed"] = plan0.stat(1)
+    res["issued_pairs_padded"] = plan0.stat(2)
+    res["groups"] = plan0.num_groups
+    res["q_tiles_packed"] = plan0.stat(6)
+    # planner alone (host)
+    t0 = time.perf_counter()
+    for _ in range(20):
+        p = pk.pack_plan(w.kv_lens, w.q_lens, token_budget=w.token_budget)
+    res["plan_us"] = (time.perf_counter() - t0) / 20 * 1e6
+    t0 = time.perf_counter()
+    for _ in range(20):
+        p = pk.pack_plan(w.kv_lens, w.q_lens, token_budget=w.token_budget)
+        p.workspace_bytes(w.Hq, w.Hkv, w.d, pk.PK_BF16)
+    res["plan_and_tables_us"] = (time.perf_counter() - t0) / 20 * 1e6
+    if with_padded:
+        avg_p, _ = _time_launches(lambda: pk.padded_prefill_attn(plan0, w.q, w.k, w.v, out, w.scale, ws), max(steps, 10))
+        res["padded_kernel_ms"] = avg_p
+        res["padded_kernel_tflops"] = flops / (avg_p * 1e-3) / 1e12
+        res["packed_over_padded"] = avg_p / avg
+    return res
+
+
+def bench_decode(w, iters, with_padded=True):
+    """Re-layout + packed decode on a paged workload; rotates over several
+    buffer copies when the working set could sit in the last-level cache."""
+    import torch
+    from paper_2602_06072_amd import binding as pk
+    res = {}
+    dev = w.q.device
+    ones = np.ones_like(w.kv_lens)
+    plan = pk.pack_plan(w.kv_lens, ones, w.prefix_ids, w.prefix_lens, w.token_budget)
+    ws = pk.new_workspace(plan, w.Hq, w.Hkv, w.d, pk.PK_BF16)
+    pk.plan_bind(plan, w.Hq, w.Hkv, w.d, pk.PK_BF16, ws)
+    kv_bytes_unique = plan.unique_tokens * w.Hkv * w.d * 2 * 2
+    ncopies = 1 if kv_bytes_unique > (1 << 30) else 4
+    bufs = [pk.new_kv_buf(plan, w.Hkv, w.d, pk.PK_BF16) for _ in range(ncopies)]
+    bt = torch.from_numpy(w.block_table).to(dev)
+    out = torch.empty(w.q.shape, dtype=torch.bfloat16, device=dev)
+    state = {"i": 0}
+
+    def reorg():
+        state["i"] = (state["i"] + 1) % ncopies
+        pk.kv_reorganize(plan, w.k_pages, w.v_pages, bt, bufs[state["i"]], ws)
+
+    for b in bufs:
+        pk.kv_reorganize(plan, w.k_pages, w.v_pages, bt, b, ws)
+    avg, mn = _time_launches(reorg, iters)
+    res["reorg_ms"] = avg
+    res["reorg_gbs"] = 2 * kv_bytes_unique / (avg * 1e-3) / 1e9
+    res["reorg_hbm_frac"] = res["reorg_gbs"] / HBM_PEAK_GBS
+
+    def dec():
+        state["i"] = (state["i"] + 1) % ncopies
+        pk.packed_decode_attn(plan, w.q, bufs[state["i"]], out, w.scale, w.Hkv, ws)
+
+    avg, mn = _time_launches(dec, iters)
+    n_parts = plan.stat(4)
+    qo_bytes = w.n * w.Hq * w.d * 4
+    part_bytes = 2 * n_parts * w.Hq * (w.d + 1) * 4
+    alg_bytes = kv_bytes_unique + qo_bytes + part_bytes
+    res["decode_ms"] = avg
+    res["decode_ms_min"] = mn
+    res["decode_gbs"] = alg_bytes / (avg * 1e-3) / 1e9
+    res["decode_hbm_frac"] = res["decode_gbs"] / HBM_PEAK_GBS
+    res["kv_bytes_unique"] = kv_bytes_unique
+    res["kv_bytes_naive"] = int(w.kv_lens.astype(np.int64).sum()) * w.Hkv * w.d * 4
+    res["alg_bytes"] = alg_bytes
+    res["groups"] = plan.num_groups
+    res["work_items"] = plan.stat(3)
+    res["split_tokens"] = plan.stat(5)
+    res["buffer_copies_rotated"] = ncopies
+    if with_padded:
+        try:
+            avg_p, _ = _time_launches(
+                lambda: pk.padded_decode_attn(plan, w.q, w.k_pages, w.v_pages, bt, out, w.scale, ws), iters)
+            res["padded_decode_ms"] = avg_p
+            res["padded_decode_gbs"] = alg_bytes / (avg_p * 1e-3) / 1e9
+            res["packed_over_padded"] = avg_p / avg
+        except pk.PackInferError as e:
+            res["padded_decode"] = str(e)
+    return res
+
+
+def cpu_baseline(w):
+    """The oracle as it stands, timed on every second query row of the batch."""
+    from oracle import attention as oa
+    rows = np.array([(i, h, t) for i in range(w.n) for t in range(0, int(w.q_lens[i]), 2)
+                     for h in range(w.Hq)], dtype=np.int32)
+    ctx = (w.kv_lens - w.q_lens).astype(np.int64)
+    pairs = int(sum(int(ctx[i]) + int(t) + 1 for (i, _, t) in rows))
+    q, k, v = w.q.cpu(), w.k.cpu(), w.v.cpu()
+    t0 = time.perf_counter()
+    _, used = oa.attention_ragged(q, k, v, w.q_lens, w.kv_lens, w.scale, rows=rows)
+    dt = time.perf_counter() - t0
+    return {"value": 4.0 * w.d * pairs / dt / 1e12, "unit": "TFLOP/s", "cores": int(used), "kind": "oracle",
+            "sample": f"every 2nd query row of every request, all {w.Hq} heads "
+                      f"({len(rows)} rows, {4.0 * w.d * pairs / 1e9:.1f} GFLOP, {dt:.1f} s, fp64 accumulate)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-extras", action="store_true", help="skip the decode / mixed-step lines")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this hot path runs on ONE GPU (no sharding, no collectives); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2602_06072_amd import binding as pk
+    from paper_2602_06072_amd import workloads as wl
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    pk.lib()                                          # fail loudly if the HIP library is missing
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    w2 = wl.config2(args.seed, device=dev)
+    r2 = bench_prefill(w2, args.steps, args.warmup)
+    extra = {"prefill_cfg2": r2}
+    if not args.no_extras:
+        w3 = wl.config3(args.seed, device=dev)
+        extra["decode_cfg3"] = bench_decode(w3, 20)
+        del w3
+        w4 = wl.config4(args.seed, device=dev)
+        extra["decode_cfg4_shared_prefix"] = bench_decode(w4, 20)
+        del w4
+        torch.cuda.empty_cache()
+        w5 = wl.config5(args.seed, device=dev)
+        extra["prefill_cfg5_70b_chunks"] = bench_prefill(w5.prefill, 5, 2)
+        extra["decode_cfg5_70b"] = bench_decode(w5.decode, 5)
+        del w5
+        torch.cuda.empty_cache()
+    line = {
+        "metric": "packed attn prefill TFLOP/s + decode KV GB/s (% roofline) vs padded",
+        "value": r2["step_tflops"], "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": r2["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "configs[1]: Llama-3-8B-shaped prefill attention layer, 64 requests, "
+                               "lognormal lengths (median 256, sigma 1.2, clip [8,8192]), Hq=32 Hkv=8 d=128, "
+                               "causal, token budget 16384", "seed": args.seed,
+                   "tokens": int(w2.q_lens.sum()), "step": "pack_plan + table upload + packed prefill kernel"},
+        "roofline": {"bound": "mfma", "achieved": r2["kernel_tflops"], "peak": MFMA_BF16_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": r2["kernel_tflops"] / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                     "kernel": "prefill_bf16_kernel<128>", "kernel_ms": r2["kernel_ms"]},
+    }
+    if not args.no_cpu:
+        line["cpu_baseline"] = cpu_baseline(w2)
+    line["extra"] = extra
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -33,6 +33,9 @@ def lib():
     if not os.path.exists(LIB_PATH):
         raise PackInferError(
             f"{LIB_PATH} is missing: build it with `python -m paper_2602_06072_amd.build`")
+    # PyTorch owns the device memory and the streams: load its HIP runtime first so that the
+    # library's libamdhip64 dependency resolves to the same, already initialised, runtime.
+    import torch  # noqa: F401
     L = ctypes.CDLL(LIB_PATH)
     vp, i32, i64, f32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float, ctypes.c_size_t
     ci = ctypes.c_int

@@ -69,8 +69,8 @@ __global__ __launch_bounds__(256, 2) void prefill_bf16_kernel(PrefillArgs a) {
                              (static_cast<int64_t>(qrow < 0 ? 0 : qrow) * a.Hq + head) * D + 8 * hlf;
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
-            uint4 raw = make_uint4(0, 0, 0, 0);
-            if (qrow >= 0) raw = *reinterpret_cast<const uint4*>(qp + 16 * s);
+            u32x4 raw = {0u, 0u, 0u, 0u};
+            if (qrow >= 0) raw = *reinterpret_cast<const u32x4*>(qp + 16 * s);
             qf[s] = __builtin_bit_cast(bf16x8, raw);
         }
     }
@@ -80,43 +80,47 @@ __global__ __launch_bounds__(256, 2) void prefill_bf16_kernel(PrefillArgs a) {
     for (int b = 0; b < DB; ++b)
 #pragma unroll
         for (int e = 0; e < 16; ++e) o[b][e] = 0.f;
+    // m: running row maximum of the RAW scores (it may lag behind the true maximum by up to
+    // kLazy / sl2, see below); l: this lane's share of sum_j exp2((s_j - m) * sl2)
     float m = -INFINITY, l = 0.f;
     const float sl2 = a.scale * kLog2e;
+    const float lazy = 8.0f / sl2;                 // rescale only when the maximum grows by > 2^8
 
-    // ---- tile loader -------------------------------------------------------
-    const uint4* kg = static_cast<const uint4*>(a.k);
-    const uint4* vg = static_cast<const uint4*>(a.v);
-    uint4 kreg[LD], vreg[LD];
-    auto gload = [&](int j) {
-        const int k_start = a.kvtiles[2 * static_cast<int64_t>(kv_first + j)];
-#pragma unroll
-        for (int i = 0; i < LD; ++i) {
-            const int idx = tid + 256 * i, row = idx / CH, c = idx % CH;
-            int64_t kr = static_cast<int64_t>(k_start) + row;
-            kr = kr < a.total_kv_rows ? kr : a.total_kv_rows - 1;
-            const int64_t off = (kr * a.Hkv + kvh) * CH + c;
-            kreg[i] = kg[off];
-            vreg[i] = vg[off];
-        }
-    };
-    auto sstore = [&](int stage) {
-        unsigned char* ks = smem + stage * SM::STAGE;
-        unsigned char* vs = ks + SM::K_BYTES;
-#pragma unroll
-        for (int i = 0; i < LD; ++i) {
-            const int idx = tid + 256 * i, row = idx / CH, c = idx % CH;
-            *reinterpret_cast<uint4*>(ks + row * SM::KP + c * 16) = kreg[i];
-            *reinterpret_cast<uint4*>(vs + row * SM::VP + c * 16) = vreg[i];
-        }
-    };
+    // ---- tile loader (registers -> LDS) -------------------------------------
+    const u32x4* kg = static_cast<const u32x4*>(a.k);
+    const u32x4* vg = static_cast<const u32x4*>(a.v);
+    const int ld_row = tid / CH, ld_c = tid % CH;  // this thread's first chunk; next ones 256/CH rows on
+    u32x4 kreg[LD], vreg[LD];
+#define PK_GLOAD(J)                                                                          \
+    {                                                                                        \
+        const int ks_ = a.kvtiles[2 * static_cast<int64_t>(kv_first + (J))];                 \
+        _Pragma("unroll") for (int i = 0; i < LD; ++i) {                                     \
+            int64_t kr = static_cast<int64_t>(ks_) + ld_row + i * (256 / CH);                \
+            kr = kr < a.total_kv_rows ? kr : a.total_kv_rows - 1;                            \
+            const int64_t off = (kr * a.Hkv + kvh) * CH + ld_c;                              \
+            kreg[i] = kg[off];                                                               \
+            vreg[i] = vg[off];                                                               \
+        }                                                                                    \
+    }
+#define PK_SSTORE(SIDX)                                                                      \
+    {                                                                                        \
+        unsigned char* ks_ = smem + (SIDX) * SM::STAGE;                                      \
+        unsigned char* vs_ = ks_ + SM::K_BYTES;                                              \
+        _Pragma("unroll") for (int i = 0; i < LD; ++i) {                                     \
+            const int row = ld_row + i * (256 / CH);                                         \
+            *reinterpret_cast<u32x4*>(ks_ + row * SM::KP + ld_c * 16) = kreg[i];             \
+            *reinterpret_cast<u32x4*>(vs_ + row * SM::VP + ld_c * 16) = vreg[i];             \
+        }                                                                                    \
+    }
 
-    gload(0);
-    sstore(0);
+    PK_GLOAD(0);
+    PK_SSTORE(0);
     __syncthreads();
 
+    const int i16 = lane & 15, gl = (lane >> 4) & 1;
     for (int j = 0; j < n_kv; ++j) {
         const int stage = j & 1;
-        if (j + 1 < n_kv) gload(j + 1);
+        if (j + 1 < n_kv) PK_GLOAD(j + 1);
         const int32_t k_start = a.kvtiles[2 * static_cast<int64_t>(kv_first + j)];
         const int32_t info = a.kvtiles[2 * static_cast<int64_t>(kv_first + j) + 1];
         const int code = (info >> (8 + 2 * wave)) & 3;       // 0 skip, 1 masked, 2 unmasked
@@ -132,12 +136,11 @@ __global__ __launch_bounds__(256, 2) void prefill_bf16_kernel(PrefillArgs a) {
                 const unsigned char* krow = ks + (32 * kb + n) * SM::KP + 16 * hlf;
 #pragma unroll
                 for (int st = 0; st < KS; ++st) {
-                    const bf16x8 kf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(krow + 32 * st));
+                    const bf16x8 kf = *reinterpret_cast<const bf16x8*>(krow + 32 * st);
                     s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[st], s[kb], 0, 0, 0);
                 }
             }
             // lane (n, hlf), register e of block kb: key k_start + 32kb + 8(e/4) + 4hlf + e%4
-            float mx = -INFINITY;
             if (code == 1) {
                 // keys past the tile's valid count belong to whatever follows in memory
                 const int hi_t = min(hi, k_start + (info & 0xFF));
@@ -146,49 +149,52 @@ __global__ __launch_bounds__(256, 2) void prefill_bf16_kernel(PrefillArgs a) {
 #pragma unroll
                     for (int e = 0; e < 16; ++e) {
                         const int key = k_start + 32 * kb + 8 * (e >> 2) + 4 * hlf + (e & 3);
-                        const float x = (key >= lo && key < hi_t) ? s[kb][e] * sl2 : -INFINITY;
-                        s[kb][e] = x;
-                        mx = fmaxf(mx, x);
-                    }
-            } else {
-#pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                    for (int e = 0; e < 16; ++e) {
-                        const float x = s[kb][e] * sl2;
-                        s[kb][e] = x;
-                        mx = fmaxf(mx, x);
+                        if (key < lo || key >= hi_t) s[kb][e] = -INFINITY;
                     }
             }
-            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            const float m_new = fmaxf(m, mx);
-            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-            const float alpha = exp2f(m - m_use);
-            m = m_new;
-            float ps = 0.f;
+            float mx = fmaxf(s[0][0], s[1][0]);
+#pragma unroll
+            for (int e = 1; e < 16; ++e) mx = fmaxf(fmaxf(mx, s[0][e]), s[1][e]);
+            {
+                const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+                mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+            }
+            // Lazy rescaling: the stored maximum is only raised when some row's maximum grew by
+            // more than `lazy`; until then p = exp2((s - m) sl2) <= 2^8, harmless in fp32/bf16,
+            // and the final o / l is unchanged because o and l use the same m.
+            if (__builtin_amdgcn_ballot_w64(mx > m + lazy) != 0 || __builtin_amdgcn_ballot_w64(m == -INFINITY) != 0) {
+                const float m_new = fmaxf(m, mx);
+                const float m_ref = (m_new == -INFINITY) ? 0.f : m_new;
+                const float alpha = __builtin_amdgcn_exp2f((m - m_ref) * sl2);   // m = -inf -> 0
+                m = m_new;
+                l *= alpha;
+#pragma unroll
+                for (int b = 0; b < DB; ++b)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) o[b][e] *= alpha;
+            }
+            const float msl = ((m == -INFINITY) ? 0.f : m) * sl2;
             bf16x8 pf[2][2];
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
-                float p[16];
-#pragma unroll
-                for (int e = 0; e < 16; ++e) { p[e] = exp2f(s[kb][e] - m_use); ps += p[e]; }
+            for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                 for (int t = 0; t < 2; ++t) {
-                    uint4 w;
-                    w.x = pack_bf16x2(p[8 * t + 0], p[8 * t + 1]); w.y = pack_bf16x2(p[8 * t + 2], p[8 * t + 3]);
-                    w.z = pack_bf16x2(p[8 * t + 4], p[8 * t + 5]); w.w = pack_bf16x2(p[8 * t + 6], p[8 * t + 7]);
-                    pf[kb][t] = __builtin_bit_cast(bf16x8, w);
+                    uint32_t w[4];
+#pragma unroll
+                    for (int x = 0; x < 4; ++x) {
+                        floatx2 pp;
+                        pp[0] = __builtin_amdgcn_exp2f(fmaf(s[kb][8 * t + 2 * x], sl2, -msl));
+                        pp[1] = __builtin_amdgcn_exp2f(fmaf(s[kb][8 * t + 2 * x + 1], sl2, -msl));
+                        const bf16x2 pb = __builtin_convertvector(pp, bf16x2);
+                        // the row sum uses the rounded probabilities, like the PV product does
+                        l = __builtin_amdgcn_fdot2_f32_bf16(pb, bf16x2{(__bf16)1.0f, (__bf16)1.0f}, l, false);
+                        w[x] = __builtin_bit_cast(uint32_t, pb);
+                    }
+                    pf[kb][t] = __builtin_bit_cast(bf16x8, u32x4{w[0], w[1], w[2], w[3]});
                 }
-            }
-            l = l * alpha + ps;
-#pragma unroll
-            for (int b = 0; b < DB; ++b)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) o[b][e] *= alpha;
             // ---- O^T += V^T . P^T --------------------------------------------
             // MFMA (kb, t) contracts keys 32kb + 16t + {4hlf..4hlf+3} and {8+4hlf..8+4hlf+3}; the
             // transpose read hands lane i of a 16-lane group column i of a 4-row x 16-column patch.
-            const int i16 = lane & 15, gl = (lane >> 4) & 1;
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -205,12 +211,17 @@ __global__ __launch_bounds__(256, 2) void prefill_bf16_kernel(PrefillArgs a) {
                     }
                 }
         }
-        if (j + 1 < n_kv) sstore(stage ^ 1);
+        if (j + 1 < n_kv) PK_SSTORE(stage ^ 1);
         __syncthreads();
     }
+#undef PK_GLOAD
+#undef PK_SSTORE
 
     // ---- epilogue ----------------------------------------------------------
-    l += __shfl_xor(l, 32, 64);
+    {
+        const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(l), __float_as_uint(l), false, false);
+        l = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
+    }
     if (qrow < 0) return;
     const float inv = l > 0.f ? 1.f / l : 0.f;
     const int64_t obase = (static_cast<int64_t>(qrow) * a.Hq + head) * D;
