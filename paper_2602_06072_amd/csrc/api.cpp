@@ -43,11 +43,29 @@ int ensure_bound(pk_plan* plan, int Hq, int Hkv, int d, int dtype, void* workspa
     }
     plan->bound_ws = workspace;
     plan->bound_bytes = workspace_bytes;
+    t.padded_uploaded = false;
     return PK_OK;
 }
 
-const int32_t* tab(const pk_plan* plan, const TableRef& r) {
-    return reinterpret_cast<const int32_t*>(static_cast<const char*>(plan->bound_ws) + r.offset);
+// The padded comparison schedule is built and copied on its first use only.
+int ensure_padded(pk_plan* plan, void* stream) {
+    DeviceTables& t = plan->tables;
+    if (!t.padded_built) build_prefill_padded(*plan, t);
+    if (t.padded_uploaded) return PK_OK;
+    if (t.padded_offset + t.host_padded.size() * sizeof(int32_t) > plan->bound_bytes)
+        return fail(PK_EINVAL, "workspace smaller than pk_workspace_bytes");
+    if (!t.host_padded.empty()) {
+        hipError_t e = hipMemcpyAsync(static_cast<char*>(plan->bound_ws) + t.padded_offset, t.host_padded.data(),
+                                      t.host_padded.size() * sizeof(int32_t), hipMemcpyHostToDevice,
+                                      static_cast<hipStream_t>(stream));
+        if (e != hipSuccess) return hip_fail("copy of the padded schedule", e);
+    }
+    t.padded_uploaded = true;
+    return PK_OK;
+}
+
+const int32_t* tab(const pk_plan* plan, const TableRef& r, size_t base = 0) {
+    return reinterpret_cast<const int32_t*>(static_cast<const char*>(plan->bound_ws) + base + r.offset);
 }
 
 }  // namespace
@@ -121,13 +139,18 @@ static int prefill_common(pk_plan* plan, const void* q, const void* k, const voi
     if (dtype == PK_F32 && d > 256) return fail(PK_EUNSUPPORTED, std::string(who) + ": fp32 path needs d <= 256");
     int rc = ensure_bound(plan, Hq, Hkv, d, dtype, workspace, workspace_bytes, stream);
     if (rc != PK_OK) return rc;
+    if (padded && dtype == PK_BF16) {
+        rc = ensure_padded(plan, stream);
+        if (rc != PK_OK) return rc;
+    }
     const DeviceTables& t = plan->tables;
     const DeviceTables::PrefillSched& s = padded ? t.padded : t.packed;
+    const size_t base = padded ? t.padded_offset : 0;
     PrefillArgs a{};
     a.q = q; a.k = k; a.v = v; a.out = out;
-    a.tiles = tab(plan, s.tiles); a.n_tiles = s.n_tiles;
-    a.row_q = tab(plan, s.row_q); a.row_lo = tab(plan, s.row_lo); a.row_hi = tab(plan, s.row_hi);
-    a.kvtiles = tab(plan, s.kvtiles);
+    a.tiles = tab(plan, s.tiles, base); a.n_tiles = s.n_tiles;
+    a.row_q = tab(plan, s.row_q, base); a.row_lo = tab(plan, s.row_lo, base); a.row_hi = tab(plan, s.row_hi, base);
+    a.kvtiles = tab(plan, s.kvtiles, base);
     a.q_start = tab(plan, t.q_start); a.kv_start = tab(plan, t.kv_start); a.n = plan->n;
     int64_t tq = 0, tkv = 0;
     for (int32_t i = 0; i < plan->n; ++i) { tq += plan->q_lens[i]; tkv += plan->kv_lens[i]; }
@@ -202,12 +225,18 @@ extern "C" int64_t pk_plan_stat(const pk_plan* plan, int what) {
     switch (what) {
         case 0: return plan->unmasked_pairs;
         case 1: return plan->tables.packed.issued_pairs;
-        case 2: return plan->tables.padded.issued_pairs;
+        case 2:
+            if (!plan->tables.padded_built && plan->tables.dtype >= 0)
+                build_prefill_padded(*plan, const_cast<pk_plan*>(plan)->tables);
+            return plan->tables.padded.issued_pairs;
         case 3: return plan->tables.n_dec_items;
         case 4: return plan->tables.n_dec_parts;
         case 5: return plan->tables.dec_split_tokens;
         case 6: return plan->tables.packed.n_tiles;
-        case 7: return plan->tables.padded.n_tiles;
+        case 7:
+            if (!plan->tables.padded_built && plan->tables.dtype >= 0)
+                build_prefill_padded(*plan, const_cast<pk_plan*>(plan)->tables);
+            return plan->tables.padded.n_tiles;
         default: return 0;
     }
 }

@@ -58,6 +58,10 @@ struct DeviceTables {
         int32_t n_tiles = 0;
         int64_t issued_pairs = 0;
     } packed, padded;
+    // padded prefill schedule: built on first use, uploaded behind the partial results
+    std::vector<int32_t> host_padded;
+    bool padded_built = false, padded_uploaded = false;
+    size_t padded_offset = 0;
     // partial results (floats) live after the tables
     size_t tables_bytes = 0;
     size_t partial_offset = 0;      // bytes
@@ -90,6 +94,7 @@ void set_error(const std::string& msg);
 
 // schedule.cpp
 void build_tables(const pk_plan& plan, int Hq, int Hkv, int d, int dtype, DeviceTables& out);
+void build_prefill_padded(const pk_plan& plan, DeviceTables& t);
 size_t kv_buf_bytes(const pk_plan& plan, int Hkv, int d, int dtype);
 
 }  // namespace pk

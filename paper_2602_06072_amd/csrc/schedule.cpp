@@ -160,138 +160,184 @@ void build_decode(const pk_plan& plan, int Hq, int Hkv, Builder& b, DeviceTables
 }
 
 // ---- prefill ---------------------------------------------------------------
-struct QRow { int32_t req, t; };       // packed row -> (request, query position); req < 0: padding
+struct QRow { int32_t req, t; };       // packed row -> (request, query position)
 
-struct TileOut {
-    std::vector<int32_t> row_q, row_lo, row_hi;   // BM entries
-    std::vector<int32_t> kv;                      // pairs
-    int64_t weight = 0;
-    int32_t n_rows = 0;
+// Flat arrays of a schedule under construction (tiles in construction order).
+struct SchedBuild {
+    std::vector<int32_t> row_q, row_lo, row_hi;   // BM entries per tile
+    std::vector<int32_t> kv;                      // (k_start, info) pairs of all tiles
+    std::vector<int32_t> kv_first, n_kv, n_rows;  // per tile
+    std::vector<int64_t> weight;                  // active (wave, key tile) pairs per tile
+    int64_t issued = 0;
 };
 
-// Builds the key-tile list of one query tile.  all_waves: the padded schedule
-// never lets a wave skip.
-TileOut make_tile(const pk_plan& plan, const std::vector<int64_t>& q_start,
-                  const std::vector<int64_t>& kv_start, const std::vector<QRow>& rows,
-                  bool all_waves, int64_t* issued) {
+// Appends one query tile (rows[0..nrows)) and its key-tile list.  all_waves: the padded
+// schedule never lets a wave skip.
+void add_tile(const pk_plan& plan, const std::vector<int64_t>& q_start,
+              const std::vector<int64_t>& kv_start, const QRow* rows, int nrows,
+              bool all_waves, SchedBuild& sb) {
     constexpr int BM = kPrefillBM, BN = kPrefillBN, WR = 32, NW = BM / WR;
-    TileOut o;
-    o.row_q.assign(BM, -1); o.row_lo.assign(BM, 0); o.row_hi.assign(BM, 0);
-    o.n_rows = static_cast<int32_t>(rows.size());
-    for (size_t i = 0; i < rows.size(); ++i) {
+    const size_t r0 = sb.row_q.size();
+    sb.row_q.resize(r0 + BM, -1); sb.row_lo.resize(r0 + BM, 0); sb.row_hi.resize(r0 + BM, 0);
+    for (int i = 0; i < nrows; ++i) {
         const int32_t rq = rows[i].req;
-        if (rq < 0) continue;
         const int64_t ctx = plan.kv_lens[rq] - plan.q_lens[rq];
-        o.row_q[i] = static_cast<int32_t>(q_start[rq] + rows[i].t);
-        o.row_lo[i] = static_cast<int32_t>(kv_start[rq]);
-        o.row_hi[i] = static_cast<int32_t>(kv_start[rq] + ctx + rows[i].t + 1);
+        sb.row_q[r0 + i] = static_cast<int32_t>(q_start[rq] + rows[i].t);
+        sb.row_lo[r0 + i] = static_cast<int32_t>(kv_start[rq]);
+        sb.row_hi[r0 + i] = static_cast<int32_t>(kv_start[rq] + ctx + rows[i].t + 1);
     }
-    // runs of rows of the same request
-    size_t i = 0;
-    while (i < rows.size()) {
+    const size_t kv0 = sb.kv.size();
+    int64_t weight = 0;
+    int i = 0;
+    while (i < nrows) {                            // runs of rows of the same request
         const int32_t rq = rows[i].req;
-        size_t j = i + 1;
-        while (j < rows.size() && rows[j].req == rq) ++j;
-        if (rq >= 0) {
-            const int64_t ks0 = kv_start[rq];
-            const int64_t ctx = plan.kv_lens[rq] - plan.q_lens[rq];
-            const int64_t kend = ks0 + ctx + rows[j - 1].t + 1;          // hi of the run's last row
-            for (int64_t ks = ks0; ks < kend; ks += BN) {
-                const int64_t ke = std::min(kend, ks + BN);
-                int32_t flags = 0;
-                for (int w = 0; w < NW; ++w) {
-                    // rows of this wave that belong to the run
-                    const size_t wa = std::max<size_t>(i, static_cast<size_t>(w) * WR);
-                    const size_t wb = std::min<size_t>(j, static_cast<size_t>(w + 1) * WR);
-                    int code = 0;
-                    if (wa < wb && ks < ks0 + ctx + rows[wb - 1].t + 1) {
-                        bool pure = true;                                 // no row of another request in the wave
-                        for (size_t x = static_cast<size_t>(w) * WR;
-                             x < std::min(rows.size(), static_cast<size_t>(w + 1) * WR); ++x)
-                            if (rows[x].req >= 0 && rows[x].req != rq) pure = false;
-                        const bool below = ke <= ks0 + ctx + rows[wa].t + 1;
-                        code = (pure && below && ke - ks == BN) ? 2 : 1;
-                    } else if (all_waves) {
-                        code = 1;
-                    }
-                    if (code) { o.weight += 1; if (issued) *issued += static_cast<int64_t>(WR) * BN; }
-                    flags |= code << (2 * w);
+        int j = i + 1;
+        while (j < nrows && rows[j].req == rq) ++j;
+        const int64_t ks0 = kv_start[rq];
+        const int64_t ctx = plan.kv_lens[rq] - plan.q_lens[rq];
+        const int64_t kend = ks0 + ctx + rows[j - 1].t + 1;              // hi of the run's last row
+        // per wave: its rows inside the run, and whether it holds rows of no other request
+        int wa[NW], wb[NW];
+        bool pure[NW];
+        for (int w = 0; w < NW; ++w) {
+            wa[w] = std::max(i, w * WR);
+            wb[w] = std::min(j, (w + 1) * WR);
+            pure[w] = i <= w * WR && std::min(nrows, (w + 1) * WR) <= j;
+        }
+        for (int64_t ks = ks0; ks < kend; ks += BN) {
+            const int64_t ke = std::min(kend, ks + BN);
+            int32_t flags = 0;
+            for (int w = 0; w < NW; ++w) {
+                int code = 0;
+                if (wa[w] < wb[w] && ks < ks0 + ctx + rows[wb[w] - 1].t + 1) {
+                    const bool below = ke <= ks0 + ctx + rows[wa[w]].t + 1;
+                    code = (pure[w] && below && ke - ks == BN) ? 2 : 1;
+                } else if (all_waves) {
+                    code = 1;
                 }
-                if (flags == 0) continue;
-                o.kv.push_back(static_cast<int32_t>(ks));
-                o.kv.push_back(static_cast<int32_t>(ke - ks) | (flags << 8));
+                weight += code != 0;
+                flags |= code << (2 * w);
             }
+            if (flags == 0) continue;
+            sb.kv.push_back(static_cast<int32_t>(ks));
+            sb.kv.push_back(static_cast<int32_t>(ke - ks) | (flags << 8));
         }
         i = j;
     }
-    return o;
+    sb.issued += weight * WR * BN;
+    sb.kv_first.push_back(static_cast<int32_t>(kv0 / 2));
+    sb.n_kv.push_back(static_cast<int32_t>((sb.kv.size() - kv0) / 2));
+    sb.n_rows.push_back(nrows);
+    sb.weight.push_back(weight);
 }
 
-void emit_sched(std::vector<TileOut>& tiles, const std::vector<int32_t>& order, Builder& b,
+void add_idle_tile(SchedBuild& sb) {               // padded grid slot of a request without that many tiles
+    sb.row_q.resize(sb.row_q.size() + kPrefillBM, -1);
+    sb.row_lo.resize(sb.row_lo.size() + kPrefillBM, 0);
+    sb.row_hi.resize(sb.row_hi.size() + kPrefillBM, 0);
+    sb.kv_first.push_back(static_cast<int32_t>(sb.kv.size() / 2));
+    sb.n_kv.push_back(0); sb.n_rows.push_back(0); sb.weight.push_back(0);
+}
+
+// Writes the tiles in the given order (key-tile lists are re-based accordingly).
+void emit_sched(const SchedBuild& sb, const std::vector<int32_t>& order, Builder& b,
                 DeviceTables::PrefillSched& s) {
+    constexpr int BM = kPrefillBM;
     std::vector<int32_t> desc, rq, rlo, rhi, kv;
+    desc.reserve(order.size() * 4);
+    rq.reserve(sb.row_q.size()); rlo.reserve(sb.row_q.size()); rhi.reserve(sb.row_q.size());
+    kv.reserve(sb.kv.size());
     for (int32_t idx : order) {
-        TileOut& t = tiles[idx];
         desc.push_back(static_cast<int32_t>(kv.size() / 2));
-        desc.push_back(static_cast<int32_t>(t.kv.size() / 2));
-        desc.push_back(t.n_rows);
+        desc.push_back(sb.n_kv[idx]);
+        desc.push_back(sb.n_rows[idx]);
         desc.push_back(0);
-        rq.insert(rq.end(), t.row_q.begin(), t.row_q.end());
-        rlo.insert(rlo.end(), t.row_lo.begin(), t.row_lo.end());
-        rhi.insert(rhi.end(), t.row_hi.begin(), t.row_hi.end());
-        kv.insert(kv.end(), t.kv.begin(), t.kv.end());
+        rq.insert(rq.end(), sb.row_q.begin() + idx * BM, sb.row_q.begin() + (idx + 1) * BM);
+        rlo.insert(rlo.end(), sb.row_lo.begin() + idx * BM, sb.row_lo.begin() + (idx + 1) * BM);
+        rhi.insert(rhi.end(), sb.row_hi.begin() + idx * BM, sb.row_hi.begin() + (idx + 1) * BM);
+        kv.insert(kv.end(), sb.kv.begin() + 2 * sb.kv_first[idx], sb.kv.begin() + 2 * (sb.kv_first[idx] + sb.n_kv[idx]));
     }
     s.n_tiles = static_cast<int32_t>(order.size());
+    s.issued_pairs = sb.issued;
     s.tiles = b.add(desc);
     s.row_q = b.add(rq); s.row_lo = b.add(rlo); s.row_hi = b.add(rhi);
     s.kvtiles = b.add(kv);
 }
 
-void build_prefill(const pk_plan& plan, const std::vector<int64_t>& q_start,
-                   const std::vector<int64_t>& kv_start, Builder& b, DeviceTables& t) {
+// packed: tiles over each group's packed row stream, heaviest tile first
+void build_prefill_packed(const pk_plan& plan, const std::vector<int64_t>& q_start,
+                          const std::vector<int64_t>& kv_start, Builder& b, DeviceTables& t) {
     constexpr int BM = kPrefillBM;
-    // packed: tiles over each group's packed row stream
-    {
-        std::vector<TileOut> tiles;
-        for (const Group& g : plan.groups) {
-            std::vector<QRow> rows;
-            for (const Member& m : g.members) {
-                for (int32_t x = 0; x < plan.q_lens[m.req]; ++x) {
-                    rows.push_back({m.req, x});
-                    if (rows.size() == BM) {
-                        tiles.push_back(make_tile(plan, q_start, kv_start, rows, false, &t.packed.issued_pairs));
-                        rows.clear();
-                    }
+    SchedBuild sb;
+    std::vector<QRow> rows;
+    rows.reserve(BM);
+    for (const Group& g : plan.groups) {
+        rows.clear();
+        for (const Member& m : g.members) {
+            for (int32_t x = 0; x < plan.q_lens[m.req]; ++x) {
+                rows.push_back({m.req, x});
+                if (rows.size() == BM) {
+                    add_tile(plan, q_start, kv_start, rows.data(), BM, false, sb);
+                    rows.clear();
                 }
             }
-            if (!rows.empty())
-                tiles.push_back(make_tile(plan, q_start, kv_start, rows, false, &t.packed.issued_pairs));
         }
-        std::vector<int32_t> order(tiles.size());
-        std::iota(order.begin(), order.end(), 0);
-        std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) {
-            return tiles[x].weight > tiles[y].weight;                    // longest first
-        });
-        emit_sched(tiles, order, b, t.packed);
+        if (!rows.empty())
+            add_tile(plan, q_start, kv_start, rows.data(), static_cast<int>(rows.size()), false, sb);
     }
-    // padded: request-aligned grid (request, tile) sized by the longest request
-    {
-        int32_t max_tiles = 0;
-        for (int32_t i = 0; i < plan.n; ++i)
-            max_tiles = std::max(max_tiles, (plan.q_lens[i] + BM - 1) / BM);
-        std::vector<TileOut> tiles;
-        for (int32_t i = 0; i < plan.n; ++i) {
-            for (int32_t tt = 0; tt < max_tiles; ++tt) {
-                std::vector<QRow> rows;
-                for (int32_t x = tt * BM; x < std::min(plan.q_lens[i], (tt + 1) * BM); ++x)
-                    rows.push_back({i, x});
-                tiles.push_back(make_tile(plan, q_start, kv_start, rows, true, &t.padded.issued_pairs));
-            }
+    std::vector<int32_t> order(sb.n_kv.size());
+    std::iota(order.begin(), order.end(), 0);
+    std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) { return sb.weight[x] > sb.weight[y]; });
+    emit_sched(sb, order, b, t.packed);
+}
+
+}  // namespace
+
+// padded: request-aligned grid (request, tile) sized by the longest request, natural order.
+// Built on first use into its own host image (uploaded behind the partial results).
+void build_prefill_padded(const pk_plan& plan, DeviceTables& t) {
+    constexpr int BM = kPrefillBM;
+    std::vector<int64_t> q_start(static_cast<size_t>(plan.n) + 1, 0), kv_start(static_cast<size_t>(plan.n) + 1, 0);
+    for (int32_t i = 0; i < plan.n; ++i) {
+        q_start[i + 1] = q_start[i] + plan.q_lens[i];
+        kv_start[i + 1] = kv_start[i] + plan.kv_lens[i];
+    }
+    int32_t max_tiles = 0;
+    for (int32_t i = 0; i < plan.n; ++i) max_tiles = std::max(max_tiles, (plan.q_lens[i] + BM - 1) / BM);
+    SchedBuild sb;
+    std::vector<QRow> rows;
+    for (int32_t i = 0; i < plan.n; ++i) {
+        for (int32_t tt = 0; tt < max_tiles; ++tt) {
+            rows.clear();
+            for (int32_t x = tt * BM; x < std::min(plan.q_lens[i], (tt + 1) * BM); ++x) rows.push_back({i, x});
+            if (rows.empty()) add_idle_tile(sb);
+            else add_tile(plan, q_start, kv_start, rows.data(), static_cast<int>(rows.size()), true, sb);
         }
-        std::vector<int32_t> order(tiles.size());
-        std::iota(order.begin(), order.end(), 0);
-        emit_sched(tiles, order, b, t.padded);
     }
+    std::vector<int32_t> order(sb.n_kv.size());
+    std::iota(order.begin(), order.end(), 0);
+    t.host_padded.clear();
+    Builder b(t.host_padded);
+    emit_sched(sb, order, b, t.padded);
+    t.host_padded.resize((t.host_padded.size() + 63) / 64 * 64, 0);
+    t.padded_built = true;
+}
+
+namespace {
+
+// Upper bound (bytes) of the padded schedule's tables, without building them.
+size_t padded_bound_bytes(const pk_plan& plan) {
+    constexpr int64_t BM = kPrefillBM, BN = kPrefillBN;
+    int64_t max_tiles = 0, kv_entries = 0;
+    for (int32_t i = 0; i < plan.n; ++i) max_tiles = std::max<int64_t>(max_tiles, (plan.q_lens[i] + BM - 1) / BM);
+    for (int32_t i = 0; i < plan.n; ++i) {
+        const int64_t ctx = plan.kv_lens[i] - plan.q_lens[i];
+        for (int64_t tt = 0; tt * BM < plan.q_lens[i]; ++tt)
+            kv_entries += (ctx + std::min<int64_t>(plan.q_lens[i], (tt + 1) * BM) + BN - 1) / BN;
+    }
+    const int64_t tiles = max_tiles * plan.n;
+    const int64_t ints = tiles * 4 + 3 * tiles * BM + 2 * kv_entries + 6 * 64;
+    return static_cast<size_t>((ints + 63) / 64 * 64) * sizeof(int32_t);
 }
 
 }  // namespace
@@ -314,12 +360,13 @@ void build_tables(const pk_plan& plan, int Hq, int Hkv, int d, int dtype, Device
     t.kv_start = b.add(std::vector<int32_t>(kv_start.begin(), kv_start.end()));
     build_reorg(plan, b, t);
     if (plan.decode_only) build_decode(plan, Hq, Hkv, b, t);
-    build_prefill(plan, q_start, kv_start, b, t);
+    build_prefill_packed(plan, q_start, kv_start, b, t);
     t.host.resize((t.host.size() + 63) / 64 * 64, 0);
     t.tables_bytes = t.host.size() * sizeof(int32_t);
     t.partial_offset = t.tables_bytes;
     t.partial_bytes = static_cast<size_t>(t.n_dec_parts) * Hq * (static_cast<size_t>(d) + 1) * sizeof(float);
-    t.total_bytes = (t.partial_offset + t.partial_bytes + 255) / 256 * 256;
+    t.padded_offset = (t.partial_offset + t.partial_bytes + 255) / 256 * 256;
+    t.total_bytes = (t.padded_offset + padded_bound_bytes(plan) + 255) / 256 * 256;
 }
 
 }  // namespace pk
