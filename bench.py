@@ -194,6 +194,18 @@ def cpu_baseline(w):
                       f"({len(rows)} rows, {4.0 * w.d * pairs / 1e9:.1f} GFLOP, {dt:.1f} s, fp64 accumulate)"}
 
 
+def profiled_traffic(tag):
+    """HBM bytes per launch measured with rocprofv3 counters (profiles/bench_hbm_traffic.txt), or None."""
+    try:
+        for line in open(os.path.join(ROOT, "profiles", "bench_hbm_traffic.txt")):
+            f = line.split()
+            if len(f) >= 5 and f[0] == "TRAFFIC" and f[1] == tag:
+                return float(f[4].split("=")[1])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -202,6 +214,8 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-extras", action="store_true", help="skip the decode / mixed-step lines")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain elementwise kernel over 1 GiB 5 times (reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this hot path runs on ONE GPU (no sharding, no collectives); use --gpus 1",
@@ -218,6 +232,14 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
 
+    if args.calibrate_copy:
+        # an elementwise kernel that reads 1 GiB and writes 1 GiB (bf16 x 2 -> bf16)
+        src = torch.ones(1 << 29, dtype=torch.bfloat16, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            torch.mul(src, 2.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
     w2 = wl.config2(args.seed, device=dev)
     r2 = bench_prefill(w2, args.steps, args.warmup)
     extra = {"prefill_cfg2": r2}
@@ -245,7 +267,8 @@ def main():
                                "causal, token budget 16384", "seed": args.seed,
                    "tokens": int(w2.q_lens.sum()), "step": "pack_plan + table upload + packed prefill kernel"},
         "roofline": {"bound": "mfma", "achieved": r2["kernel_tflops"], "peak": MFMA_BF16_PEAK_TFLOPS,
-                     "unit": "TFLOP/s", "frac": r2["kernel_tflops"] / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                     "unit": "TFLOP/s", "frac": r2["kernel_tflops"] / MFMA_BF16_PEAK_TFLOPS,
+                     "traffic": profiled_traffic("prefill_cfg2_packed") if args.seed == 0 else None,
                      "kernel": "prefill_bf16_kernel<128>", "kernel_ms": r2["kernel_ms"]},
     }
     if not args.no_cpu:
