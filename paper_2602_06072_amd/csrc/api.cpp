@@ -196,8 +196,8 @@ extern "C" int pk_packed_decode_attn(pk_plan* plan, const void* q, const void* k
     DecodeArgs a{};
     a.q = q; a.kv_buf = kv_buf; a.out = out;
     a.items = tab(plan, t.dec_items); a.n_items = t.n_dec_items; a.n_wide = t.n_dec_wide;
-    a.members = tab(plan, t.dec_members);
-    a.req_part_start = tab(plan, t.dec_req_part_start); a.req_parts = tab(plan, t.dec_req_parts);
+    a.members = tab(plan, t.dec_members); a.member_slot = tab(plan, t.dec_member_slot);
+    a.req_part_start = tab(plan, t.dec_req_part_start);
     a.req_seg = tab(plan, t.dec_req_seg);
     a.part_o = reinterpret_cast<float*>(static_cast<char*>(workspace) + t.partial_offset);
     a.part_lse = a.part_o + static_cast<size_t>(t.n_dec_parts) * Hq * d;

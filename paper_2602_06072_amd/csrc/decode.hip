@@ -16,30 +16,45 @@
 namespace pk {
 namespace {
 
-template <int D, int NT>
-__global__ __launch_bounds__(64) void decode_bf16_kernel(DecodeArgs a) {
+template <int D, int NT, bool PREFETCH>
+__device__ __forceinline__ void decode_body(const DecodeArgs& a, const int item, const int kvh) {
     constexpr int KS = D / 32;                 // K steps per 16-key sub-tile
     constexpr int VT = D / 16;                 // V column blocks
-    constexpr int TILE_U4 = 2 * 32 * (D / 8);  // uint4 per tile (K part + V part)
+    constexpr int NK = 2 * KS;                 // 16-byte chunks per lane of a tile's K part
+    constexpr int TILE_U4 = 2 * 32 * (D / 8);  // 16-byte chunks per tile (K part + V part)
     const int lane = threadIdx.x, n = lane & 15, g = lane >> 4;
-    const int kvh = blockIdx.y;
     const int r = a.Hq / a.Hkv;
-    const int32_t* it = a.items + 8 * static_cast<int64_t>(blockIdx.x);
-    const int tok_begin = it[0], tok_end = it[1], mem_first = it[2], n_mem = it[3], part_base = it[4];
+    const int32_t* it = a.items + 8 * static_cast<int64_t>(item);
+    const int tok_begin = it[0], tok_end = it[1], mem_first = it[2], n_mem = it[3];
+    const int64_t n_tiles = a.buf_tokens / 32;
+    const u32x4* base = static_cast<const u32x4*>(a.kv_buf) + static_cast<int64_t>(kvh) * n_tiles * TILE_U4 + lane;
+    const int b0 = tok_begin / 32, b1 = (tok_end + 31) / 32;
+
+    // Two register sets: the loads of tile b+1 are in flight while tile b is processed.  The
+    // first tile is requested before anything else so that it overlaps the query set-up.
+    u32x4 ka[NK], va[VT], kb_[NK], vb_[VT];
+#define PK_LOAD_TILE(KR, VR, B)                                                      \
+    {                                                                                \
+        const u32x4* tile_ = base + static_cast<int64_t>(B) * TILE_U4;               \
+        _Pragma("unroll") for (int i = 0; i < NK; ++i) KR[i] = __builtin_nontemporal_load(tile_ + i * 64);        \
+        _Pragma("unroll") for (int i = 0; i < VT; ++i) VR[i] = __builtin_nontemporal_load(tile_ + (NK + i) * 64); \
+    }
+    PK_LOAD_TILE(ka, va, b0);
 
     // query operand (B side): lane (n, g) holds Q[row n][32s + 8g .. +8]
     bf16x8 qf[NT][KS];
-    int req_of[NT], hq_of[NT];
+    int req_of[NT], hq_of[NT], slot_of[NT];
 #pragma unroll
     for (int c = 0; c < NT; ++c) {
         const int mi = (c * 16 + n) / r;
         const bool ok = mi < n_mem;
         req_of[c] = ok ? a.members[mem_first + mi] : -1;
+        slot_of[c] = ok ? a.member_slot[mem_first + mi] : -1;
         hq_of[c] = kvh * r + (c * 16 + n) % r;
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
-            uint4 raw = make_uint4(0, 0, 0, 0);
-            if (ok) raw = *reinterpret_cast<const uint4*>(
+            u32x4 raw = {0u, 0u, 0u, 0u};
+            if (ok) raw = *reinterpret_cast<const u32x4*>(
                 static_cast<const uint16_t*>(a.q) +
                 (static_cast<int64_t>(req_of[c]) * a.Hq + hq_of[c]) * D + 32 * s + 8 * g);
             qf[c][s] = __builtin_bit_cast(bf16x8, raw);
@@ -54,30 +69,17 @@ __global__ __launch_bounds__(64) void decode_bf16_kernel(DecodeArgs a) {
 #pragma unroll
         for (int t = 0; t < VT; ++t) o[c][t] = floatx4{0.f, 0.f, 0.f, 0.f};
     }
-
-    const int64_t n_tiles = a.buf_tokens / 32;
-    const uint4* base = static_cast<const uint4*>(a.kv_buf) + static_cast<int64_t>(kvh) * n_tiles * TILE_U4;
-    const int b0 = tok_begin / 32, b1 = (tok_end + 31) / 32;
     const float sl2 = a.scale * kLog2e;
 
-    for (int b = b0; b < b1; ++b) {
-        const uint4* tile = base + static_cast<int64_t>(b) * TILE_U4;
-        uint4 kraw[2][KS], vraw[VT];
-#pragma unroll
-        for (int u = 0; u < 2; ++u)
-#pragma unroll
-            for (int s = 0; s < KS; ++s) kraw[u][s] = tile[(u * KS + s) * 64 + lane];
-#pragma unroll
-        for (int t = 0; t < VT; ++t) vraw[t] = tile[2 * KS * 64 + t * 64 + lane];
-
+    auto process = [&](const u32x4 (&kraw)[NK], const u32x4 (&vraw)[VT], int b) {
         const bool edge = (b * 32 < tok_begin) || (b * 32 + 32 > tok_end);
 #pragma unroll
         for (int c = 0; c < NT; ++c) {
             floatx4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int s = 0; s < KS; ++s) {
-                s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kraw[0][s]), qf[c][s], s0, 0, 0, 0);
-                s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kraw[1][s]), qf[c][s], s1, 0, 0, 0);
+                s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kraw[s]), qf[c][s], s0, 0, 0, 0);
+                s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kraw[KS + s]), qf[c][s], s1, 0, 0, 0);
             }
             // lane (n, g) now holds scores of row n against keys 32b + 16u + 4g + j
             float x[8];
@@ -97,16 +99,20 @@ __global__ __launch_bounds__(64) void decode_bf16_kernel(DecodeArgs a) {
             mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
             const float m_new = fmaxf(m[c], mx);
             const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-            const float alpha = exp2f(m[c] - m_use);      // 0 on the first tile
-            float p[8], ps = 0.f;
+            const float alpha = __builtin_amdgcn_exp2f(m[c] - m_use);      // 0 on the first tile
+            float ps = 0.f;
+            uint32_t pw[4];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) { p[j] = exp2f(x[j] - m_use); ps += p[j]; }
+            for (int j = 0; j < 4; ++j) {
+                floatx2 pp;
+                pp[0] = __builtin_amdgcn_exp2f(x[2 * j] - m_use);
+                pp[1] = __builtin_amdgcn_exp2f(x[2 * j + 1] - m_use);
+                ps += pp[0] + pp[1];
+                pw[j] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pp, bf16x2));
+            }
             l[c] = l[c] * alpha + ps;
             m[c] = m_new;
-            uint4 pw;
-            pw.x = pack_bf16x2(p[0], p[1]); pw.y = pack_bf16x2(p[2], p[3]);
-            pw.z = pack_bf16x2(p[4], p[5]); pw.w = pack_bf16x2(p[6], p[7]);
-            const bf16x8 pf = __builtin_bit_cast(bf16x8, pw);
+            const bf16x8 pf = __builtin_bit_cast(bf16x8, u32x4{pw[0], pw[1], pw[2], pw[3]});
 #pragma unroll
             for (int t = 0; t < VT; ++t) {
                 floatx4 acc = o[c][t];
@@ -114,7 +120,24 @@ __global__ __launch_bounds__(64) void decode_bf16_kernel(DecodeArgs a) {
                 o[c][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vraw[t]), pf, acc, 0, 0, 0);
             }
         }
+    };
+
+    if (PREFETCH) {
+        for (int b = b0; b < b1; b += 2) {
+            if (b + 1 < b1) PK_LOAD_TILE(kb_, vb_, b + 1);
+            process(ka, va, b);
+            if (b + 1 < b1) {
+                if (b + 2 < b1) PK_LOAD_TILE(ka, va, b + 2);
+                process(kb_, vb_, b + 1);
+            }
+        }
+    } else {
+        for (int b = b0; b < b1; ++b) {
+            if (b > b0) PK_LOAD_TILE(ka, va, b);
+            process(ka, va, b);
+        }
     }
+#undef PK_LOAD_TILE
 
 #pragma unroll
     for (int c = 0; c < NT; ++c) {
@@ -122,8 +145,22 @@ __global__ __launch_bounds__(64) void decode_bf16_kernel(DecodeArgs a) {
         lt += __shfl_xor(lt, 16, 64);
         lt += __shfl_xor(lt, 32, 64);
         if (req_of[c] < 0) continue;
-        const int slot = part_base + (c * 16 + n) / r;
         const float inv = lt > 0.f ? 1.f / lt : 0.f;
+        if (slot_of[c] < 0) {
+            // the only work item of this request: write the final output
+            const int64_t dst = (static_cast<int64_t>(req_of[c]) * a.Hq + hq_of[c]) * D;
+#pragma unroll
+            for (int t = 0; t < VT; ++t) {
+                const float x0 = o[c][t][0] * inv, x1 = o[c][t][1] * inv, x2 = o[c][t][2] * inv, x3 = o[c][t][3] * inv;
+                if (a.out_f32)
+                    *reinterpret_cast<float4*>(static_cast<float*>(a.out) + dst + 16 * t + 4 * g) = make_float4(x0, x1, x2, x3);
+                else
+                    *reinterpret_cast<uint2*>(static_cast<uint16_t*>(a.out) + dst + 16 * t + 4 * g) =
+                        make_uint2(pack_bf16x2(x0, x1), pack_bf16x2(x2, x3));
+            }
+            continue;
+        }
+        const int slot = slot_of[c];
         float* po = a.part_o + (static_cast<int64_t>(slot) * a.Hq + hq_of[c]) * D;
 #pragma unroll
         for (int t = 0; t < VT; ++t) {
@@ -136,43 +173,86 @@ __global__ __launch_bounds__(64) void decode_bf16_kernel(DecodeArgs a) {
     }
 }
 
-// out[i, h, :] = sum_j exp(lse_j - lse) o_j over the request's partial slots.
+// Work items with at most 16 query rows: one column tile, tile loads double buffered.
 template <int D>
-__global__ __launch_bounds__(D) void decode_merge_kernel(DecodeArgs a) {
-    const int i = blockIdx.x, h = blockIdx.y, c = threadIdx.x;
+__global__ __launch_bounds__(64) void decode_bf16_kernel(DecodeArgs a) {
+    decode_body<D, 1, true>(a, blockIdx.x, blockIdx.y);
+}
+
+// Batches with shared prefixes: the first n_wide work items carry 17..32 query rows (two column
+// tiles).  Both kinds run in ONE launch so that the short prefix pass and the suffix pass fill
+// the chip together; occupancy, not register prefetch, hides the load latency here.
+template <int D>
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void decode_bf16_mixed_kernel(DecodeArgs a) {
+    if (static_cast<int>(blockIdx.x) < a.n_wide) decode_body<D, 2, false>(a, blockIdx.x, blockIdx.y);
+    else decode_body<D, 1, false>(a, blockIdx.x, blockIdx.y);
+}
+
+// out[i, h, :] = sum_j exp(lse_j - lse) o_j over the request's partial slots (consecutive).
+// Workgroup = (request, head), 4 waves; wave w takes slots w, w+4, ... four at a time (all
+// loads of a batch are issued before the first use), every lane owns D/64 columns; the four
+// partial sums meet in LDS.  Requests with a single work item were written by the decode
+// kernel and are skipped.
+template <int D>
+__global__ __launch_bounds__(256) void decode_merge_kernel(DecodeArgs a) {
+    constexpr int CPL = D / 64;                    // columns per lane
+    __shared__ float red_acc[4][D];
+    __shared__ float red_tot[4];
+    const int i = blockIdx.x, h = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int p0 = a.req_part_start[i], p1 = a.req_part_start[i + 1];
+    if (p1 <= p0) return;
+    const float* lse_base = a.part_lse + h;
     float mx = -INFINITY;
-    for (int p = p0; p < p1; ++p)
-        mx = fmaxf(mx, a.part_lse[static_cast<int64_t>(a.req_parts[p]) * a.Hq + h]);
-    float acc = 0.f, tot = 0.f;
-    for (int p = p0; p < p1; ++p) {
-        const int64_t slot = a.req_parts[p];
-        const float lse = a.part_lse[slot * a.Hq + h];
-        const float w = (lse == -INFINITY) ? 0.f : expf(lse - mx);
-        tot += w;
-        acc = fmaf(w, a.part_o[(slot * a.Hq + h) * D + c], acc);
+    for (int p = p0 + lane; p < p1; p += 64) mx = fmaxf(mx, lse_base[static_cast<int64_t>(p) * a.Hq]);
+    mx = wave_max(mx);
+    float acc[CPL], tot = 0.f;
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) acc[c] = 0.f;
+    for (int p = p0 + wave; p < p1; p += 16) {
+        float lse[4], v[4][CPL];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int q = p + 4 * u;
+            lse[u] = q < p1 ? lse_base[static_cast<int64_t>(q) * a.Hq] : -INFINITY;
+#pragma unroll
+            for (int c = 0; c < CPL; ++c)
+                v[u][c] = q < p1 ? a.part_o[(static_cast<int64_t>(q) * a.Hq + h) * D + lane * CPL + c] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const float w = (lse[u] == -INFINITY) ? 0.f : expf(lse[u] - mx);
+            tot += w;
+#pragma unroll
+            for (int c = 0; c < CPL; ++c) acc[c] = fmaf(w, v[u][c], acc[c]);
+        }
     }
-    const float o = tot > 0.f ? acc / tot : 0.f;
-    const int64_t dst = (static_cast<int64_t>(i) * a.Hq + h) * D + c;
-    if (a.out_f32) static_cast<float*>(a.out)[dst] = o;
-    else static_cast<uint16_t*>(a.out)[dst] = float_to_bf16_bits(o);
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) red_acc[wave][lane * CPL + c] = acc[c];
+    if (lane == 0) red_tot[wave] = tot;
+    __syncthreads();
+    if (wave != 0) return;
+    tot = red_tot[0] + red_tot[1] + red_tot[2] + red_tot[3];
+    const float inv = tot > 0.f ? 1.f / tot : 0.f;
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) {
+        const int col = lane * CPL + c;
+        const float o = (red_acc[0][col] + red_acc[1][col] + red_acc[2][col] + red_acc[3][col]) * inv;
+        const int64_t dst = (static_cast<int64_t>(i) * a.Hq + h) * D + col;
+        if (a.out_f32) static_cast<float*>(a.out)[dst] = o;
+        else static_cast<uint16_t*>(a.out)[dst] = float_to_bf16_bits(o);
+    }
 }
 
 template <int D>
 int launch_d(const DecodeArgs& a, hipStream_t st) {
-    if (a.n_wide > 0) {                        // items with 17..32 query rows: two column tiles
-        dim3 grid(static_cast<unsigned>(a.n_wide), static_cast<unsigned>(a.Hkv));
-        hipLaunchKernelGGL((decode_bf16_kernel<D, 2>), grid, dim3(64), 0, st, a);
-    }
-    if (a.n_items > a.n_wide) {
-        DecodeArgs b = a;
-        b.items = a.items + 8 * static_cast<int64_t>(a.n_wide);
-        dim3 grid(static_cast<unsigned>(a.n_items - a.n_wide), static_cast<unsigned>(a.Hkv));
-        hipLaunchKernelGGL((decode_bf16_kernel<D, 1>), grid, dim3(64), 0, st, b);
+    if (a.n_items > 0) {
+        dim3 grid(static_cast<unsigned>(a.n_items), static_cast<unsigned>(a.Hkv));
+        if (a.n_wide > 0) hipLaunchKernelGGL(decode_bf16_mixed_kernel<D>, grid, dim3(64), 0, st, a);
+        else hipLaunchKernelGGL(decode_bf16_kernel<D>, grid, dim3(64), 0, st, a);
     }
     if (a.n > 0)
         hipLaunchKernelGGL(decode_merge_kernel<D>, dim3(static_cast<unsigned>(a.n), static_cast<unsigned>(a.Hq)),
-                           dim3(D), 0, st, a);
+                           dim3(256), 0, st, a);
     return static_cast<int>(hipGetLastError());
 }
 

@@ -19,8 +19,8 @@ int launch_reorg_f32(const ReorgArgs& a, void* stream);
 struct DecodeArgs {
     const void* q; const void* kv_buf; void* out;
     const int32_t* items; int32_t n_items; int32_t n_wide;   // the first n_wide items have > 16 query rows
-    const int32_t* members;
-    const int32_t* req_part_start; const int32_t* req_parts;
+    const int32_t* members; const int32_t* member_slot;
+    const int32_t* req_part_start;
     const int32_t* req_seg;
     float* part_o; float* part_lse;
     int64_t buf_tokens; int32_t n; int Hq; int Hkv; int d; float scale; int out_f32;

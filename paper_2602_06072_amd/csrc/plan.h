@@ -46,8 +46,8 @@ struct DeviceTables {
     // decode
     TableRef dec_items;             // [n_items][8]
     TableRef dec_members;           // request ids of the work items' rows
-    TableRef dec_req_part_start;    // [n+1]
-    TableRef dec_req_parts;         // partial slot ids per request
+    TableRef dec_member_slot;       // partial slot of each (item, member), -1: the item writes the output
+    TableRef dec_req_part_start;    // [n+1] first slot of each request (slots of a request are consecutive)
     TableRef dec_req_seg;           // [n][4] absolute prefix_off, L_P, suffix_off, L_Q
     int32_t n_dec_items = 0, n_dec_wide = 0, n_dec_parts = 0, dec_split_tokens = 0;
     // prefill (packed and padded schedules share one format)

@@ -76,8 +76,8 @@ void build_decode(const pk_plan& plan, int Hq, int Hkv, Builder& b, DeviceTables
     const int r = Hq / Hkv;
     const int max_members = std::max(1, kDecodeMaxRows / r);
     // split length: enough work items to fill the chip, long enough to amortise the partials
-    int64_t split = (plan.unique_tokens * Hkv / 16384 + kDecodeBlock - 1) / kDecodeBlock * kDecodeBlock;
-    split = std::min<int64_t>(std::max<int64_t>(split, 128), 2048);
+    int64_t split = (plan.unique_tokens * Hkv / 4096 + kDecodeBlock - 1) / kDecodeBlock * kDecodeBlock;
+    split = std::min<int64_t>(std::max<int64_t>(split, 256), 2048);
     split = env_int("PK_DECODE_SPLIT", static_cast<int>(split));
     split = (split + kDecodeBlock - 1) / kDecodeBlock * kDecodeBlock;
     t.dec_split_tokens = static_cast<int32_t>(split);
@@ -128,34 +128,38 @@ void build_decode(const pk_plan& plan, int Hq, int Hkv, Builder& b, DeviceTables
     });
     t.n_dec_wide = 0;
     for (const Item& it : items) t.n_dec_wide += wide(it) ? 1 : 0;
-    std::vector<int32_t> flat, members;
-    std::vector<std::vector<int32_t>> parts_of(static_cast<size_t>(plan.n));
+    // Partial slots: the slots of one request are consecutive (the merge streams them without
+    // indirection); a request covered by a single work item gets no slot: that item writes the
+    // final output itself (slot -1).
+    std::vector<int32_t> n_items_of(static_cast<size_t>(plan.n), 0), start(static_cast<size_t>(plan.n) + 1, 0);
+    for (const Item& it : items)
+        for (int32_t rq : it.reqs) ++n_items_of[static_cast<size_t>(rq)];
     int32_t n_parts = 0;
+    for (int32_t i = 0; i < plan.n; ++i) {
+        start[static_cast<size_t>(i)] = n_parts;
+        if (n_items_of[static_cast<size_t>(i)] > 1) n_parts += n_items_of[static_cast<size_t>(i)];
+    }
+    start[static_cast<size_t>(plan.n)] = n_parts;
+    std::vector<int32_t> next_slot(start.begin(), start.end() - 1);
+    std::vector<int32_t> flat, members, member_slot;
     for (int32_t idx : order) {
         const Item& it = items[idx];
         flat.push_back(static_cast<int32_t>(it.a));
         flat.push_back(static_cast<int32_t>(it.e));
         flat.push_back(static_cast<int32_t>(members.size()));
         flat.push_back(static_cast<int32_t>(it.reqs.size()));
-        flat.push_back(n_parts);
-        flat.push_back(0); flat.push_back(0); flat.push_back(0);
+        flat.push_back(0); flat.push_back(0); flat.push_back(0); flat.push_back(0);
         for (int32_t rq : it.reqs) {
             members.push_back(rq);
-            parts_of[static_cast<size_t>(rq)].push_back(n_parts++);
+            member_slot.push_back(n_items_of[static_cast<size_t>(rq)] > 1 ? next_slot[static_cast<size_t>(rq)]++ : -1);
         }
     }
-    std::vector<int32_t> start(static_cast<size_t>(plan.n) + 1, 0), parts;
-    for (int32_t i = 0; i < plan.n; ++i) {
-        start[static_cast<size_t>(i)] = static_cast<int32_t>(parts.size());
-        parts.insert(parts.end(), parts_of[static_cast<size_t>(i)].begin(), parts_of[static_cast<size_t>(i)].end());
-    }
-    start[static_cast<size_t>(plan.n)] = static_cast<int32_t>(parts.size());
     t.n_dec_items = static_cast<int32_t>(items.size());
     t.n_dec_parts = n_parts;
     t.dec_items = b.add(flat);
     t.dec_members = b.add(members);
+    t.dec_member_slot = b.add(member_slot);
     t.dec_req_part_start = b.add(start);
-    t.dec_req_parts = b.add(parts);
     t.dec_req_seg = b.add(req_seg);
 }
 
