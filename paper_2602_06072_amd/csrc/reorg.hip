@@ -43,32 +43,32 @@ __global__ __launch_bounds__(256) void reorg_bf16_kernel(ReorgArgs a) {
     for (int t = 0; t < 32; ++t) any |= src_s[t] >= 0;
     if (!any) return;                             // tile without valid tokens: not written
 
-    const uint4* kp = static_cast<const uint4*>(a.k_pages);
-    const uint4* vp = static_cast<const uint4*>(a.v_pages);
+    const u32x4* kp = static_cast<const u32x4*>(a.k_pages);
+    const u32x4* vp = static_cast<const u32x4*>(a.v_pages);
     for (int x = tid; x < 32 * CH; x += 256) {
         const int tok = x / CH, c = x % CH;
         const int64_t src = src_s[tok];
-        uint4 kv = make_uint4(0, 0, 0, 0), vv = kv;
-        if (src >= 0) {
+        u32x4 kv = {0u, 0u, 0u, 0u}, vv = kv;
+        if (src >= 0) {                           // pages are read once: keep them out of the caches
             const int64_t off = (src * a.Hkv + h) * CH + c;
-            kv = kp[off];
-            vv = vp[off];
+            kv = __builtin_nontemporal_load(kp + off);
+            vv = __builtin_nontemporal_load(vp + off);
         }
-        *reinterpret_cast<uint4*>(k_s + tok * KP + c * 16) = kv;
+        *reinterpret_cast<u32x4*>(k_s + tok * KP + c * 16) = kv;
         uint2* vd = reinterpret_cast<uint2*>(v_s + tok * VP + c * 16);
-        vd[0] = make_uint2(vv.x, vv.y);
-        vd[1] = make_uint2(vv.z, vv.w);
+        vd[0] = make_uint2(vv[0], vv[1]);
+        vd[1] = make_uint2(vv[2], vv[3]);
     }
     __syncthreads();
 
     const int64_t n_tiles = a.buf_tokens / 32;
-    uint4* tile = static_cast<uint4*>(a.kv_buf) +
+    u32x4* tile = static_cast<u32x4*>(a.kv_buf) +
                   (static_cast<int64_t>(h) * n_tiles + blk) * (2 * 32 * CH);
     // K part: chunk (u, s, l)[j] = K[16u + l%16][32s + 8(l/16) + j]
     for (int o = tid; o < 32 * CH; o += 256) {
         const int l = o & 63, s = (o >> 6) % (D / 32), u = o / (64 * (D / 32));
         const int tok = 16 * u + (l & 15), c = 4 * s + (l >> 4);
-        tile[o] = *reinterpret_cast<const uint4*>(k_s + tok * KP + c * 16);
+        __builtin_nontemporal_store(*reinterpret_cast<const u32x4*>(k_s + tok * KP + c * 16), tile + o);
     }
     // V part: chunk (t, l)[j] = V[kappa(l/16, j)][16t + l%16]
     for (int o = tid; o < 32 * CH; o += 256) {
@@ -80,12 +80,12 @@ __global__ __launch_bounds__(256) void reorg_bf16_kernel(ReorgArgs a) {
             const int tok = j < 4 ? 4 * g + j : 16 + 4 * g + (j - 4);
             e[j] = *reinterpret_cast<const uint16_t*>(v_s + tok * VP + col * 2);
         }
-        uint4 w;
-        w.x = e[0] | (static_cast<uint32_t>(e[1]) << 16);
-        w.y = e[2] | (static_cast<uint32_t>(e[3]) << 16);
-        w.z = e[4] | (static_cast<uint32_t>(e[5]) << 16);
-        w.w = e[6] | (static_cast<uint32_t>(e[7]) << 16);
-        tile[32 * CH + o] = w;
+        u32x4 w;
+        w[0] = e[0] | (static_cast<uint32_t>(e[1]) << 16);
+        w[1] = e[2] | (static_cast<uint32_t>(e[3]) << 16);
+        w[2] = e[4] | (static_cast<uint32_t>(e[5]) << 16);
+        w[3] = e[6] | (static_cast<uint32_t>(e[7]) << 16);
+        __builtin_nontemporal_store(w, tile + 32 * CH + o);
     }
 }
 
