@@ -13,6 +13,8 @@
 // operand layout of the second.  K/V tiles are staged through LDS (double
 // buffered, one barrier per tile); global loads of tile j+1 are issued before
 // the math of tile j.  MFMA-bound: 4*D flops per (query, key) pair.
+#include <cstdlib>
+
 #include "common.hip.h"
 #include "kernels.h"
 
@@ -96,9 +98,9 @@ __global__ __launch_bounds__(256, 2) void prefill_bf16_kernel(PrefillArgs a) {
     for (int i = 0; i < LD; ++i)
         ld_off[i] = static_cast<int>((ld_row + i * (256 / CH)) * row_bytes + kvh * D * 2 + ld_c * 16);
     u32x4 kreg[LD], vreg[LD];
-#define PK_GLOAD(J)                                                                          \
+#define PK_GLOAD(KSTART)                                                                     \
     {                                                                                        \
-        const int64_t ks_ = a.kvtiles[2 * static_cast<int64_t>(kv_first + (J))];             \
+        const int64_t ks_ = (KSTART);                                                        \
         const int64_t left_ = (a.total_kv_rows - ks_) * row_bytes;                           \
         const int nrec_ = static_cast<int>(left_ > 0x7FFFFFFFll ? 0x7FFFFFFFll : left_);     \
         const __amdgpu_buffer_rsrc_t rk_ = __builtin_amdgcn_make_buffer_rsrc(                \
@@ -121,32 +123,53 @@ __global__ __launch_bounds__(256, 2) void prefill_bf16_kernel(PrefillArgs a) {
         }                                                                                    \
     }
 
-    PK_GLOAD(0);
+    // Entries (first key row, info) of the tile list are needed as scalars.  Loads issued after a
+    // barrier are not scalarised by the compiler and their latency would sit in every iteration,
+    // so they run through a window: e0 / e1 hold tiles j, j+1 and the entry of j+2 is in flight.
+    const int32_t* kvt = a.kvtiles + 2 * static_cast<int64_t>(kv_first);
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    auto entry_load = [&](int j) -> int2 {
+        return *reinterpret_cast<const int2*>(kvt + 2 * (j < n_kv ? j : n_kv - 1));
+    };
+    int e0s, e0i, e1s, e1i;
+    {
+        const int2 x0 = entry_load(0), x1 = entry_load(1);
+        e0s = __builtin_amdgcn_readfirstlane(x0.x); e0i = __builtin_amdgcn_readfirstlane(x0.y);
+        e1s = __builtin_amdgcn_readfirstlane(x1.x); e1i = __builtin_amdgcn_readfirstlane(x1.y);
+    }
+    PK_GLOAD(e0s);
     PK_SSTORE(0);
     __syncthreads();
 
     const int i16 = lane & 15, gl = (lane >> 4) & 1;
     for (int j = 0; j < n_kv; ++j) {
         const int stage = j & 1;
-        if (j + 1 < n_kv) PK_GLOAD(j + 1);
-        const int32_t k_start = a.kvtiles[2 * static_cast<int64_t>(kv_first + j)];
-        const int32_t info = a.kvtiles[2 * static_cast<int64_t>(kv_first + j) + 1];
-        const int code = (info >> (8 + 2 * wave)) & 3;       // 0 skip, 1 masked, 2 unmasked
+        if (j + 1 < n_kv) PK_GLOAD(e1s);
+        const int2 e2 = entry_load(j + 2);
+        const int32_t k_start = e0s, info = e0i;
+        const int code = (info >> (8 + 2 * wave_u)) & 3;     // 0 skip, 1 masked, 2 unmasked
         if (code != 0) {
             const unsigned char* ks = smem + stage * SM::STAGE;
             const unsigned char* vs = ks + SM::K_BYTES;
             // ---- S^T = K . Q^T: two blocks of 32 keys -----------------------
+            // All operand reads of a phase are issued before its first MFMA (sched_barrier keeps the
+            // scheduler from sinking them back next to their uses): the LDS latency is paid once
+            // per phase instead of once per MFMA.
             floatx16 s[2];
+            {
+                bf16x8 kf[2][KS];
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
+                for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) s[kb][e] = 0.f;
-                const unsigned char* krow = ks + (32 * kb + n) * SM::KP + 16 * hlf;
+                    for (int st = 0; st < KS; ++st)
+                        kf[kb][st] = *reinterpret_cast<const bf16x8*>(ks + (32 * kb + n) * SM::KP + 16 * hlf + 32 * st);
+                __builtin_amdgcn_sched_barrier(0);
+                const floatx16 zero = {};
 #pragma unroll
-                for (int st = 0; st < KS; ++st) {
-                    const bf16x8 kf = *reinterpret_cast<const bf16x8*>(krow + 32 * st);
-                    s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[st], s[kb], 0, 0, 0);
-                }
+                for (int st = 0; st < KS; ++st)
+#pragma unroll
+                    for (int kb = 0; kb < 2; ++kb)
+                        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kb][st], qf[st], st == 0 ? zero : s[kb], 0, 0, 0);
             }
             // lane (n, hlf), register e of block kb: key k_start + 32kb + 8(e/4) + 4hlf + e%4
             if (code == 1) {
@@ -204,7 +227,8 @@ __global__ __launch_bounds__(256, 2) void prefill_bf16_kernel(PrefillArgs a) {
             // MFMA (kb, t) contracts keys 32kb + 16t + {4hlf..4hlf+3} and {8+4hlf..8+4hlf+3}; the
             // transpose read hands lane i of a 16-lane group column i of a 4-row x 16-column patch.
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
+            for (int kb = 0; kb < 2; ++kb) {
+                bf16x8 vf[2][DB];
 #pragma unroll
                 for (int t = 0; t < 2; ++t) {
                     const int key0 = 32 * kb + 16 * t + 4 * hlf + (i16 >> 2);
@@ -214,11 +238,20 @@ __global__ __launch_bounds__(256, 2) void prefill_bf16_kernel(PrefillArgs a) {
                         const unsigned char* p0 = vs + key0 * SM::VP + col * 2;
                         const bf16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)(p0));
                         const bf16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)(p0 + 8 * SM::VP));
-                        const bf16x8 vf = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
-                        o[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[kb][t], o[b], 0, 0, 0);
+                        vf[t][b] = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
                     }
                 }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+#pragma unroll
+                    for (int b = 0; b < DB; ++b)
+                        o[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[t][b], pf[kb][t], o[b], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
+        e0s = e1s; e0i = e1i;
+        e1s = __builtin_amdgcn_readfirstlane(e2.x); e1i = __builtin_amdgcn_readfirstlane(e2.y);
         if (j + 1 < n_kv) PK_SSTORE(stage ^ 1);
         __syncthreads();
     }
@@ -273,8 +306,12 @@ int launch_p(const PrefillArgs& a, hipStream_t st) {
 
 }  // namespace
 
+int launch_prefill_bf16_pipe(const PrefillArgs& a, void* stream);
+
 int launch_prefill_bf16(const PrefillArgs& a, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
+    static const bool use_pipe = [] { const char* e = getenv("PK_PREFILL_PIPE"); return e && e[0] == '1'; }();
+    if (a.d == 128 && use_pipe) return launch_prefill_bf16_pipe(a, stream);
     if (a.d == 128) return launch_p<128>(a, st);
     if (a.d == 64) return launch_p<64>(a, st);
     return static_cast<int>(hipErrorInvalidValue);
