@@ -214,10 +214,34 @@ extern "C" int pk_padded_decode_attn(pk_plan* plan, const void* q,
                                      void* out, float scale, int Hq, int Hkv, int d,
                                      int dtype, int out_dtype,
                                      void* workspace, size_t workspace_bytes, void* stream) {
-    (void)plan; (void)q; (void)k_pages; (void)v_pages; (void)block_table; (void)max_blocks_per_req;
-    (void)page_size; (void)num_blocks; (void)out; (void)scale; (void)Hq; (void)Hkv; (void)d;
-    (void)dtype; (void)out_dtype; (void)workspace; (void)workspace_bytes; (void)stream;
-    return fail(PK_EUNSUPPORTED, "pk_padded_decode_attn: not built yet");
+    std::string why;
+    if (!plan) return fail(PK_EINVAL, "pk_padded_decode_attn: plan is NULL");
+    if (plan->n == 0) return PK_OK;
+    if (!plan->decode_only) return fail(PK_EINVAL, "pk_padded_decode_attn: the plan must have q_len == 1 for every request");
+    if (!q || !k_pages || !v_pages || !block_table || !out) return fail(PK_EINVAL, "pk_padded_decode_attn: NULL pointer");
+    if (page_size <= 0 || num_blocks <= 0) return fail(PK_EINVAL, "pk_padded_decode_attn: page_size and num_blocks must be positive");
+    if (!shape_ok(Hq, Hkv, d, dtype, why)) return fail(PK_EINVAL, "pk_padded_decode_attn: " + why);
+    if (out_dtype != PK_BF16 && out_dtype != PK_F32) return fail(PK_EINVAL, "pk_padded_decode_attn: bad out_dtype");
+    if (dtype != PK_BF16) return fail(PK_EUNSUPPORTED, "pk_padded_decode_attn: bf16 only");
+    if (d != 64 && d != 128) return fail(PK_EUNSUPPORTED, "pk_padded_decode_attn: needs d in {64,128}");
+    if (Hq / Hkv > 16) return fail(PK_EUNSUPPORTED, "pk_padded_decode_attn: needs Hq/Hkv <= 16");
+    int32_t max_len = 0;
+    for (int32_t L : plan->kv_lens) max_len = L > max_len ? L : max_len;
+    if (static_cast<int64_t>(max_blocks_per_req) * page_size < max_len)
+        return fail(PK_EINVAL, "pk_padded_decode_attn: max_blocks_per_req too small for the longest request");
+    int rc = ensure_bound(plan, Hq, Hkv, d, dtype, workspace, workspace_bytes, stream);
+    if (rc != PK_OK) return rc;
+    const DeviceTables& t = plan->tables;
+    PagedDecodeArgs a{};
+    a.q = q; a.k_pages = k_pages; a.v_pages = v_pages; a.out = out;
+    a.block_table = block_table; a.max_blocks = max_blocks_per_req; a.page_size = page_size; a.num_blocks = num_blocks;
+    a.kv_start = tab(plan, t.kv_start);
+    a.n = plan->n; a.n_splits = t.pad_n_splits; a.split_tokens = t.pad_split_tokens;
+    a.part_o = reinterpret_cast<float*>(static_cast<char*>(workspace) + t.partial_offset);
+    a.part_lse = a.part_o + static_cast<size_t>(plan->n) * t.pad_n_splits * Hq * d;
+    a.Hq = Hq; a.Hkv = Hkv; a.d = d; a.scale = scale; a.out_f32 = out_dtype == PK_F32;
+    const int e = launch_padded_decode_bf16(a, stream);
+    return e ? hip_fail("pk_padded_decode_attn", e) : PK_OK;
 }
 
 extern "C" int64_t pk_plan_stat(const pk_plan* plan, int what) {

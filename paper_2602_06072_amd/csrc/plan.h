@@ -50,6 +50,7 @@ struct DeviceTables {
     TableRef dec_req_part_start;    // [n+1] first slot of each request (slots of a request are consecutive)
     TableRef dec_req_seg;           // [n][4] absolute prefix_off, L_P, suffix_off, L_Q
     int32_t n_dec_items = 0, n_dec_wide = 0, n_dec_parts = 0, dec_split_tokens = 0;
+    int32_t pad_split_tokens = 0, pad_n_splits = 0;   // padded decode comparison: uniform splits
     // prefill (packed and padded schedules share one format)
     struct PrefillSched {
         TableRef tiles;             // [n_tiles][4] kv_first, n_kv, n_rows, reserved

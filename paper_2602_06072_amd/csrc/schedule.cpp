@@ -369,6 +369,17 @@ void build_tables(const pk_plan& plan, int Hq, int Hkv, int d, int dtype, Device
     t.tables_bytes = t.host.size() * sizeof(int32_t);
     t.partial_offset = t.tables_bytes;
     t.partial_bytes = static_cast<size_t>(t.n_dec_parts) * Hq * (static_cast<size_t>(d) + 1) * sizeof(float);
+    if (plan.decode_only) {
+        // the padded comparison kernel keeps (request, split) partials in the same region: at most
+        // 16 splits, each a multiple of 32 tokens and at least 256 tokens long
+        int32_t max_len = 0;
+        for (int32_t L : plan.kv_lens) max_len = std::max(max_len, L);
+        int32_t split = std::max(256, ((max_len + 15) / 16 + 31) / 32 * 32);
+        t.pad_split_tokens = split;
+        t.pad_n_splits = (max_len + split - 1) / split;
+        const size_t pad_bytes = static_cast<size_t>(plan.n) * t.pad_n_splits * Hq * (static_cast<size_t>(d) + 1) * sizeof(float);
+        t.partial_bytes = std::max(t.partial_bytes, pad_bytes);
+    }
     t.padded_offset = (t.partial_offset + t.partial_bytes + 255) / 256 * 256;
     t.total_bytes = (t.padded_offset + padded_bound_bytes(plan) + 255) / 256 * 256;
 }

@@ -108,6 +108,13 @@ def test_decode_small(use_f32, case):
     got, plan, _ = run_decode(w, use_f32, headroom=headroom)
     want = H.oracle_paged_decode(w, use_f32)
     H.assert_close(got, want, 1 if use_f32 else 0, f"decode {case}")
+    if not use_f32:                                # in-run comparison kernel: paged, uniform splits
+        ws = pk.new_workspace(plan, w.Hq, w.Hkv, w.d, pk.PK_BF16)
+        out = torch.full(w.q.shape, float("nan"), dtype=torch.float32, device=DEV)
+        pk.padded_decode_attn(plan, w.q, w.k_pages, w.v_pages, torch.from_numpy(w.block_table).to(DEV),
+                              out, w.scale, ws)
+        torch.cuda.synchronize()
+        H.assert_close(out.cpu().numpy(), want, 0, f"padded decode {case}")
 
 
 def test_decode_bf16_output_and_many_members():
@@ -169,3 +176,82 @@ def test_empty_batch_is_a_no_op():
     ws = pk.new_workspace(plan, 4, 2, 128, pk.PK_BF16)
     pk.packed_prefill_attn(plan, q, q[:, :2], q[:, :2], q.float(), 1.0, ws)
     torch.cuda.synchronize()
+
+
+# ------------------------------------------------- benchmark configurations at full size
+def _sample_requests(lens, rng, k=6):
+    """A few requests covering the extremes and the middle of the length mix."""
+    order = np.argsort(lens)
+    pick = {int(order[0]), int(order[-1]), int(order[len(order) // 2])}
+    pick.update(int(x) for x in rng.choice(len(lens), size=min(k, len(lens)), replace=False))
+    return sorted(pick)
+
+
+@pytest.mark.parametrize("cfg", ["cfg3", "cfg4"])
+def test_decode_configs_full_size(cfg):
+    """Configurations 3 and 4 at full size, in the launch configuration bench.py times;
+    every request is checked for 3/4 (the oracle needs a few seconds)."""
+    w = wl.config3(0, device=DEV) if cfg == "cfg3" else wl.config4(0, device=DEV)
+    got, plan, _ = run_decode(w, False, out_f32=False)
+    rng = np.random.default_rng(0)
+    reqs = _sample_requests(w.kv_lens, rng, k=24)
+    want = H.oracle_paged_decode(w, False, reqs)
+    H.assert_close(got[reqs], want, 0, f"{cfg} packed decode")
+    ws = pk.new_workspace(plan, w.Hq, w.Hkv, w.d, pk.PK_BF16)
+    out = torch.full(w.q.shape, float("nan"), dtype=torch.bfloat16, device=DEV)
+    pk.padded_decode_attn(plan, w.q, w.k_pages, w.v_pages, torch.from_numpy(w.block_table).to(DEV), out, w.scale, ws)
+    torch.cuda.synchronize()
+    H.assert_close(out.float().cpu().numpy()[reqs], want, 0, f"{cfg} padded decode")
+    assert np.all(np.isfinite(got))
+    if cfg == "cfg4":                                      # families co-located, prefix stored once
+        assert plan.unique_tokens < int(w.kv_lens.sum()) // 4
+
+
+def test_config2_prefill_full_size_sampled_rows():
+    """Configuration 2 at full size: sampled (request, head, row) outputs against the oracle,
+    plus properties that hold for every row."""
+    w = wl.config2(0, device=DEV)
+    got, plan = run_prefill(w, False, out_f32=False)
+    rng = np.random.default_rng(1)
+    rows = []
+    for i in _sample_requests(w.q_lens, rng, k=10):
+        L = int(w.q_lens[i])
+        for t in sorted({0, L - 1, L // 2, int(rng.integers(0, L)), int(rng.integers(0, L))}):
+            for h in (0, 5, 31):
+                rows.append((i, h, t))
+    want = H.oracle_ragged(w, False, rows=rows)
+    qs = w.q_start
+    sel = np.stack([got[qs[i] + t, h] for (i, h, t) in rows])
+    H.assert_close(sel, want, 0, "cfg2 sampled rows")
+    assert np.all(np.isfinite(got))
+    # first causal row of every request returns v[0] of its KV head (up to bf16 rounding of the output)
+    v = w.v.float().cpu().numpy()
+    ks = w.kv_start
+    for i in range(w.n):
+        assert np.max(np.abs(got[qs[i], 7] - v[ks[i], 7 // 4])) <= 2e-2
+    got_pad, _ = run_prefill(w, False, padded=True, out_f32=False)
+    selp = np.stack([got_pad[qs[i] + t, h] for (i, h, t) in rows])
+    H.assert_close(selp, want, 0, "cfg2 padded sampled rows")
+
+
+def test_config5_mixed_step_sampled():
+    """Configuration 5 (70B shape, chunked prefill with context + long decode rows), reduced
+    request counts so that the pool fits quickly; same per-request shapes and length mix."""
+    w = wl.config5(0, device=DEV, chunks=6, decodes=48)
+    got, plan = run_prefill(w.prefill, False, out_f32=False)
+    rng = np.random.default_rng(2)
+    rows = []
+    for i in range(w.prefill.n):
+        L = int(w.prefill.q_lens[i])
+        for t in (0, L - 1, int(rng.integers(0, L))):
+            rows.append((i, int(rng.integers(0, 64)), t))
+    want = H.oracle_ragged(w.prefill, False, rows=rows)
+    qs = w.prefill.q_start
+    sel = np.stack([got[qs[i] + t, h] for (i, h, t) in rows])
+    H.assert_close(sel, want, 0, "cfg5 prefill sampled rows")
+    d = w.decode
+    gotd, pland, _ = run_decode(d, False, out_f32=False)
+    reqs = _sample_requests(d.kv_lens, rng, k=8)
+    wantd = H.oracle_paged_decode(d, False, reqs)
+    H.assert_close(gotd[reqs], wantd, 0, "cfg5 decode")
+    assert np.all(np.isfinite(gotd))
