@@ -2,7 +2,9 @@
 #include <hip/hip_runtime_api.h>
 
 #include <cstring>
+#include <mutex>
 #include <string>
+#include <vector>
 
 #include "kernels.h"
 #include "plan.h"
@@ -26,6 +28,47 @@ bool shape_ok(int Hq, int Hkv, int d, int dtype, std::string& why) {
     return true;
 }
 
+// Pinned host staging for the table copies.  A copy from pageable memory blocks the host until the
+// stream has drained; from pinned memory it is asynchronous, so the planning of the next batch
+// overlaps the kernels of the current one.  Buffers are recycled once the event recorded behind
+// their copy has completed; the pool only grows while every buffer is still in flight.
+struct Staging {
+    void* ptr = nullptr;
+    size_t cap = 0;
+    hipEvent_t done = nullptr;
+    bool used = false;                              // an event has been recorded for it
+};
+std::mutex g_staging_mutex;
+std::vector<Staging> g_staging;
+
+Staging* staging_acquire(size_t bytes) {
+    std::lock_guard<std::mutex> lock(g_staging_mutex);
+    for (Staging& s : g_staging)
+        if (s.cap >= bytes && (!s.used || hipEventQuery(s.done) == hipSuccess)) return &s;
+    if (g_staging.size() >= 64) return nullptr;     // fall back to a pageable copy
+    Staging s;
+    s.cap = (bytes + (1u << 20) - 1) >> 20 << 20;
+    if (hipHostMalloc(&s.ptr, s.cap, hipHostMallocDefault) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
+    if (hipEventCreateWithFlags(&s.done, hipEventDisableTiming) != hipSuccess) {
+        (void)hipGetLastError(); (void)hipHostFree(s.ptr); return nullptr;
+    }
+    g_staging.reserve(64);                          // pointers into the vector stay valid
+    g_staging.push_back(s);
+    return &g_staging.back();
+}
+
+int copy_tables(void* dst, const void* src, size_t bytes, void* stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    Staging* s = staging_acquire(bytes);
+    if (!s) return static_cast<int>(hipMemcpyAsync(dst, src, bytes, hipMemcpyHostToDevice, st));
+    std::memcpy(s->ptr, src, bytes);
+    hipError_t e = hipMemcpyAsync(dst, s->ptr, bytes, hipMemcpyHostToDevice, st);
+    if (e != hipSuccess) return static_cast<int>(e);
+    e = hipEventRecord(s->done, st);
+    s->used = true;
+    return static_cast<int>(e);
+}
+
 // Makes sure the plan's device tables for this shape live in `workspace`.
 int ensure_bound(pk_plan* plan, int Hq, int Hkv, int d, int dtype, void* workspace,
                  size_t workspace_bytes, void* stream) {
@@ -37,9 +80,8 @@ int ensure_bound(pk_plan* plan, int Hq, int Hkv, int d, int dtype, void* workspa
     if (!same_shape) build_tables(*plan, Hq, Hkv, d, dtype, t);
     if (workspace_bytes < t.total_bytes) return fail(PK_EINVAL, "workspace smaller than pk_workspace_bytes");
     if (t.tables_bytes) {
-        hipError_t e = hipMemcpyAsync(workspace, t.host.data(), t.tables_bytes, hipMemcpyHostToDevice,
-                                      static_cast<hipStream_t>(stream));
-        if (e != hipSuccess) return hip_fail("pk_plan_bind (copy of tables)", e);
+        const int e = copy_tables(workspace, t.host.data(), t.tables_bytes, stream);
+        if (e != 0) return hip_fail("pk_plan_bind (copy of tables)", e);
     }
     plan->bound_ws = workspace;
     plan->bound_bytes = workspace_bytes;
@@ -55,10 +97,9 @@ int ensure_padded(pk_plan* plan, void* stream) {
     if (t.padded_offset + t.host_padded.size() * sizeof(int32_t) > plan->bound_bytes)
         return fail(PK_EINVAL, "workspace smaller than pk_workspace_bytes");
     if (!t.host_padded.empty()) {
-        hipError_t e = hipMemcpyAsync(static_cast<char*>(plan->bound_ws) + t.padded_offset, t.host_padded.data(),
-                                      t.host_padded.size() * sizeof(int32_t), hipMemcpyHostToDevice,
-                                      static_cast<hipStream_t>(stream));
-        if (e != hipSuccess) return hip_fail("copy of the padded schedule", e);
+        const int e = copy_tables(static_cast<char*>(plan->bound_ws) + t.padded_offset, t.host_padded.data(),
+                                  t.host_padded.size() * sizeof(int32_t), stream);
+        if (e != 0) return hip_fail("copy of the padded schedule", e);
     }
     t.padded_uploaded = true;
     return PK_OK;
