@@ -310,8 +310,8 @@ int launch_prefill_bf16_pipe(const PrefillArgs& a, void* stream);
 
 int launch_prefill_bf16(const PrefillArgs& a, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
-    static const bool use_pipe = [] { const char* e = getenv("PK_PREFILL_PIPE"); return e && e[0] == '1'; }();
-    if (a.d == 128 && use_pipe) return launch_prefill_bf16_pipe(a, stream);
+    static const bool use_staged = [] { const char* e = getenv("PK_PREFILL_STAGED"); return e && e[0] == '1'; }();
+    if (a.d == 128 && !use_staged) return launch_prefill_bf16_pipe(a, stream);
     if (a.d == 128) return launch_p<128>(a, st);
     if (a.d == 64) return launch_p<64>(a, st);
     return static_cast<int>(hipErrorInvalidValue);

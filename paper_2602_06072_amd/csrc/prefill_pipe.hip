@@ -14,6 +14,9 @@
 //     under the exponentials.  K is therefore staged two tiles ahead of the
 //     softmax and V zero tiles ahead; each has two LDS stages and there is
 //     one barrier per tile.
+#include <cstdlib>
+#include <type_traits>
+
 #include "common.hip.h"
 #include "kernels.h"
 
@@ -201,6 +204,185 @@ __device__ __forceinline__ float steady_step(floatx16 (&s_next)[2], floatx16 (&s
     return alpha;
 }
 
+// What a workgroup works on, and this lane's share of it.
+struct WorkUnit {
+    int head, kvh, n_kv, wave, lane, n, hlf;
+    int qrow, lo, hi;                  // this lane's query row (-1: padding) and its key range [lo, hi)
+    const int32_t* kvt;                // key-tile list of the query tile: (first key row, info) pairs
+    int64_t row_bytes;                 // bytes between consecutive K/V rows in global memory
+};
+
+// Decodes the workgroup id, loads the row metadata and the Q operand, derives the lane offsets.
+// Returns false for grid padding and for query tiles without key tiles.
+__device__ __forceinline__ bool setup(const PrefillArgs& a, WorkUnit& u, LaneOffsets& off, bf16x8 (&qf)[KS]) {
+    const int r = a.Hq / a.Hkv;
+    int tile;
+    if (a.xcd_swizzle) {               // see prefill.hip: the r heads of a KV head stay on one XCD
+        const int x = blockIdx.x, c = x & 7, y = x >> 3, j = y % r, slot = y / r;
+        const int64_t p = static_cast<int64_t>(slot) * 8 + c;
+        if (p >= static_cast<int64_t>(a.n_tiles) * a.Hkv) return false;
+        tile = static_cast<int>(p / a.Hkv); u.kvh = static_cast<int>(p % a.Hkv); u.head = u.kvh * r + j;
+    } else {
+        tile = blockIdx.x / a.Hq; u.head = blockIdx.x % a.Hq; u.kvh = u.head / r;
+    }
+    const int32_t* desc = a.tiles + 4 * static_cast<int64_t>(tile);
+    u.n_kv = desc[1];
+    if (u.n_kv == 0) return false;
+    u.kvt = a.kvtiles + 2 * static_cast<int64_t>(desc[0]);
+    const int tid = threadIdx.x;
+    u.lane = tid & 63; u.n = u.lane & 31; u.hlf = u.lane >> 5;
+    u.wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int rr = tile * BM + u.wave * 32 + u.n;
+    u.qrow = a.row_q[rr]; u.lo = a.row_lo[rr]; u.hi = a.row_hi[rr];
+    u.row_bytes = static_cast<int64_t>(a.Hkv) * ROWB;
+
+    const int fl = swz(u.n);
+#pragma unroll
+    for (int st = 0; st < KS; ++st) off.k[st] = u.n * ROWB + (((2 * st + u.hlf) ^ fl) << 4);
+    const int i16 = u.lane & 15, gl = (u.lane >> 4) & 1, r4 = i16 >> 2;
+    const int f1 = (r4 << 2) | u.hlf;  // rows +8: (hlf + 2) & 3 = hlf ^ 2, i.e. chunk ^ 2, byte offset ^ 32
+    const int rowl = 4 * u.hlf + r4, byte = (i16 & 1) * 8;
+#pragma unroll
+    for (int b = 0; b < DB; ++b) {
+        const int c = 4 * b + 2 * gl + ((i16 & 3) >> 1);
+        off.v1[b] = rowl * ROWB + ((c ^ f1) << 4) + byte;
+    }
+    const int r_in = u.lane >> 4, pos = u.lane & 15;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int row = 16 * u.wave + 4 * q + r_in;
+        off.g[q] = static_cast<int>(row * u.row_bytes + u.kvh * ROWB + ((pos ^ swz(row)) << 4));
+    }
+    // Q operand: lane (n, hlf) holds Q[row n][16s + 8hlf .. +8]
+    const uint16_t* qp = static_cast<const uint16_t*>(a.q) +
+                         (static_cast<int64_t>(u.qrow < 0 ? 0 : u.qrow) * a.Hq + u.head) * D + 8 * u.hlf;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+        u32x4 raw = {0u, 0u, 0u, 0u};
+        if (u.qrow >= 0) raw = *reinterpret_cast<const u32x4*>(qp + 16 * s);
+        qf[s] = __builtin_bit_cast(bf16x8, raw);
+    }
+    return true;
+}
+
+// o / l to global memory; lane (n, hlf) owns columns 32b + 8q + 4hlf .. +3 of its query row.
+__device__ __forceinline__ void store_output(const PrefillArgs& a, const WorkUnit& u, const floatx16 (&o)[DB], float l) {
+    {
+        const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(l), __float_as_uint(l), false, false);
+        l = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
+    }
+    if (u.qrow < 0) return;
+    const float inv = l > 0.f ? 1.f / l : 0.f;
+    const int64_t obase = (static_cast<int64_t>(u.qrow) * a.Hq + u.head) * D;
+#pragma unroll
+    for (int b = 0; b < DB; ++b)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+            const int col = 32 * b + 8 * q4 + 4 * u.hlf;
+            const float x0 = o[b][4 * q4] * inv, x1 = o[b][4 * q4 + 1] * inv;
+            const float x2 = o[b][4 * q4 + 2] * inv, x3 = o[b][4 * q4 + 3] * inv;
+            if (a.out_f32) {
+                *reinterpret_cast<float4*>(static_cast<float*>(a.out) + obase + col) = make_float4(x0, x1, x2, x3);
+            } else {
+                *reinterpret_cast<uint2*>(static_cast<uint16_t*>(a.out) + obase + col) =
+                    make_uint2(pack_bf16x2(x0, x1), pack_bf16x2(x2, x3));
+            }
+        }
+}
+
+// copies the tile that starts at key row KSTART of `src` (a.k or a.v) into the LDS stage DST:
+// four 1-KiB wave instructions per wave, each lane fetching the chunk that belongs at its
+// (swizzled) LDS position; rows past the end of the array arrive as zeros
+#define PK_COPY_TILE(SRC, KSTART, DST)                                                       \
+    {                                                                                        \
+        const int64_t ks_ = (KSTART);                                                        \
+        const int64_t left_ = (a.total_kv_rows - ks_) * u.row_bytes;                         \
+        const __amdgpu_buffer_rsrc_t rs_ = __builtin_amdgcn_make_buffer_rsrc(                \
+            const_cast<char*>(static_cast<const char*>(SRC)) + ks_ * u.row_bytes, 0,         \
+            static_cast<int>(left_ > 0x7FFFFFFFll ? 0x7FFFFFFFll : left_), 0x00020000);      \
+        _Pragma("unroll") for (int q = 0; q < 4; ++q)                                        \
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(                                        \
+                rs_, (lds_void_ptr)((DST) + u.wave * 4096 + q * 1024), 16, off.g[q], 0, 0, 0); \
+    }
+#define PK_WAIT_ALL_COPIES() __builtin_amdgcn_s_waitcnt(0x0F70)      /* vmcnt(0) */
+#define PK_CODE(INFO) (((INFO) >> (8 + 2 * u.wave)) & 3)          /* 0 skip, 1 masked, 2 unmasked */
+
+// ---------------------------------------------------------------------------------------------
+// Kernel A (default): two workgroups per CU, two LDS stages per operand, plain tile loop.  The
+// copies of tile j+1 are requested before the math of tile j; the other workgroup of the CU
+// covers the wait at the end of the iteration.
+__global__ __launch_bounds__(256, 2) void prefill_bf16_dma_kernel(PrefillArgs a) {
+    __shared__ __align__(1024) unsigned char k_lds0[TILE_BYTES];
+    __shared__ __align__(1024) unsigned char k_lds1[TILE_BYTES];
+    __shared__ __align__(1024) unsigned char v_lds0[TILE_BYTES];
+    __shared__ __align__(1024) unsigned char v_lds1[TILE_BYTES];
+    WorkUnit u;
+    LaneOffsets off;
+    bf16x8 qf[KS];
+    if (!setup(a, u, off, qf)) return;
+    const int n_kv = u.n_kv;
+    const __attribute__((address_space(4))) int32_t* kvt_c =
+        (const __attribute__((address_space(4))) int32_t*)(u.kvt);
+
+    floatx16 o[DB];
+#pragma unroll
+    for (int b = 0; b < DB; ++b)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) o[b][e] = 0.f;
+    float m = -INFINITY, l = 0.f;
+    const float sl2 = a.scale * kLog2e;
+    const float lazy = 8.0f / sl2;
+
+    int ks_cur = kvt_c[0], info_cur = kvt_c[1];
+    int ks_next = kvt_c[n_kv > 1 ? 2 : 0], info_next = kvt_c[n_kv > 1 ? 3 : 1];
+    PK_COPY_TILE(a.k, ks_cur, k_lds0);
+    PK_COPY_TILE(a.v, ks_cur, v_lds0);
+    PK_WAIT_ALL_COPIES();
+    __syncthreads();
+
+    auto iteration = [&](int j, unsigned char* k_cur, unsigned char* v_cur, unsigned char* k_nxt, unsigned char* v_nxt) {
+        if (j + 1 < n_kv) {
+            PK_COPY_TILE(a.k, ks_next, k_nxt);
+            PK_COPY_TILE(a.v, ks_next, v_nxt);
+        }
+        const int jj = j + 2 < n_kv ? j + 2 : n_kv - 1;
+        const int ks_nn = kvt_c[2 * jj], info_nn = kvt_c[2 * jj + 1];      // scalar loads, used next iteration
+        const int code = PK_CODE(info_cur);
+        const int k_start = ks_cur;
+        const int hi_t = min(u.hi, k_start + (info_cur & 0xFF));   // keys past the tile's valid count are foreign
+        // the tile step exists twice so that unmasked tiles do not pay for the mask
+        auto tile_step = [&](auto masked_tag) {
+            constexpr bool MASKED = decltype(masked_tag)::value;
+            floatx16 s[2];
+            bf16x8 p[2][2];
+            bool rescale;
+            qk_tile(s, qf, k_cur, off);
+            const float alpha = softmax_tile<MASKED>(s, p, m, l, sl2, lazy, u.lo, hi_t, k_start, u.hlf, &rescale);
+            if (rescale) {                          // rare after the first tiles (wave-uniform)
+#pragma unroll
+                for (int b = 0; b < DB; ++b)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) o[b][e] *= alpha;
+            }
+            pv_tile(o, p, v_cur, off);
+        };
+        if (code == 2) tile_step(std::false_type{});
+        else if (code == 1) tile_step(std::true_type{});
+        ks_cur = ks_next; info_cur = info_next;
+        ks_next = ks_nn; info_next = info_nn;
+        PK_WAIT_ALL_COPIES();
+        __syncthreads();
+    };
+    for (int j = 0; j < n_kv; j += 2) {
+        iteration(j, k_lds0, v_lds0, k_lds1, v_lds1);
+        if (j + 1 < n_kv) iteration(j + 1, k_lds1, v_lds1, k_lds0, v_lds0);
+    }
+    store_output(a, u, o, l);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Kernel B (experimental, PK_PREFILL_PIPE=1): one workgroup per CU, four LDS stages per operand,
+// software-pipelined tile loop (see the head of this file).
 __global__ __launch_bounds__(256, 1) void prefill_bf16_pipe_kernel(PrefillArgs a) {
     // four stages each for K and V (128 KiB: one workgroup per CU); separate arrays so that the
     // copy into one stage is known not to alias the reads of another
@@ -213,79 +395,12 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_pipe_kernel(PrefillArgs a
     __shared__ __align__(1024) unsigned char v_lds2[TILE_BYTES];
     __shared__ __align__(1024) unsigned char v_lds3[TILE_BYTES];
 
-    // ---- work unit (see prefill.hip) ---------------------------------------
-    const int r = a.Hq / a.Hkv;
-    int tile, head, kvh;
-    if (a.xcd_swizzle) {
-        const int x = blockIdx.x, c = x & 7, y = x >> 3, j = y % r, slot = y / r;
-        const int64_t p = static_cast<int64_t>(slot) * 8 + c;
-        if (p >= static_cast<int64_t>(a.n_tiles) * a.Hkv) return;
-        tile = static_cast<int>(p / a.Hkv); kvh = static_cast<int>(p % a.Hkv); head = kvh * r + j;
-    } else {
-        tile = blockIdx.x / a.Hq; head = blockIdx.x % a.Hq; kvh = head / r;
-    }
-    const int32_t* desc = a.tiles + 4 * static_cast<int64_t>(tile);
-    const int kv_first = desc[0], n_kv = desc[1];
-    if (n_kv == 0) return;
-    const int32_t* kvt = a.kvtiles + 2 * static_cast<int64_t>(kv_first);
-
-    const int tid = threadIdx.x, lane = tid & 63, n = lane & 31, hlf = lane >> 5;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int rr = tile * BM + wave * 32 + n;
-    const int qrow = a.row_q[rr], lo = a.row_lo[rr], hi = a.row_hi[rr];
-
-    // ---- per-lane offsets --------------------------------------------------
+    WorkUnit u;
     LaneOffsets off;
-    {
-        const int fl = swz(n);
-#pragma unroll
-        for (int st = 0; st < KS; ++st) off.k[st] = n * ROWB + (((2 * st + hlf) ^ fl) << 4);
-        const int i16 = lane & 15, gl = (lane >> 4) & 1, r4 = i16 >> 2;
-        const int f1 = (r4 << 2) | hlf;            // rows +8: (hlf + 2) & 3 = hlf ^ 2, i.e. chunk ^ 2, byte offset ^ 32
-        const int rowl = 4 * hlf + r4, byte = (i16 & 1) * 8;
-#pragma unroll
-        for (int b = 0; b < DB; ++b) {
-            const int c = 4 * b + 2 * gl + ((i16 & 3) >> 1);
-            off.v1[b] = rowl * ROWB + ((c ^ f1) << 4) + byte;
-        }
-        const int64_t row_bytes = static_cast<int64_t>(a.Hkv) * ROWB;
-        const int r_in = lane >> 4, pos = lane & 15;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int row = 16 * wave + 4 * q + r_in;
-            off.g[q] = static_cast<int>(row * row_bytes + kvh * ROWB + ((pos ^ swz(row)) << 4));
-        }
-    }
-    const int64_t row_bytes = static_cast<int64_t>(a.Hkv) * ROWB;
-
-    // copies tile J of `src` (a.k or a.v) into the LDS stage `dst`: four 1-KiB wave instructions
-    // per wave, each lane fetching the chunk that belongs at its (swizzled) LDS position
-#define PK_COPY_TILE(SRC, KSTART, DST)                                                       \
-    {                                                                                        \
-        const int64_t ks_ = (KSTART);                                                        \
-        const int64_t left_ = (a.total_kv_rows - ks_) * row_bytes;                           \
-        const __amdgpu_buffer_rsrc_t rs_ = __builtin_amdgcn_make_buffer_rsrc(                \
-            const_cast<char*>(static_cast<const char*>(SRC)) + ks_ * row_bytes, 0,           \
-            static_cast<int>(left_ > 0x7FFFFFFFll ? 0x7FFFFFFFll : left_), 0x00020000);      \
-        _Pragma("unroll") for (int q = 0; q < 4; ++q)                                        \
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(                                        \
-                rs_, (lds_void_ptr)((DST) + wave * 4096 + q * 1024), 16, off.g[q], 0, 0, 0); \
-    }
-#define PK_WAIT_ALL_COPIES() __builtin_amdgcn_s_waitcnt(0x0F70)      /* vmcnt(0) */
-#define PK_CODE(INFO) (((INFO) >> (8 + 2 * wave)) & 3)            /* 0 skip, 1 masked, 2 unmasked */
-
-    // ---- Q operand: lane (n, hlf) holds Q[row n][16s + 8hlf .. +8] ----------
     bf16x8 qf[KS];
-    {
-        const uint16_t* qp = static_cast<const uint16_t*>(a.q) +
-                             (static_cast<int64_t>(qrow < 0 ? 0 : qrow) * a.Hq + head) * D + 8 * hlf;
-#pragma unroll
-        for (int s = 0; s < KS; ++s) {
-            u32x4 raw = {0u, 0u, 0u, 0u};
-            if (qrow >= 0) raw = *reinterpret_cast<const u32x4*>(qp + 16 * s);
-            qf[s] = __builtin_bit_cast(bf16x8, raw);
-        }
-    }
+    if (!setup(a, u, off, qf)) return;
+    const int n_kv = u.n_kv, hlf = u.hlf, lo = u.lo, hi = u.hi;
+    const int32_t* kvt = u.kvt;
 
     floatx16 o[DB];
 #pragma unroll
@@ -379,33 +494,12 @@ __global__ __launch_bounds__(256, 1) void prefill_bf16_pipe_kernel(PrefillArgs a
         const int last = (n_kv - 1) & 3;
         pv_tile(o, p_prev, last == 0 ? v_lds0 : last == 1 ? v_lds1 : last == 2 ? v_lds2 : v_lds3, off);
     }
+    store_output(a, u, o, l);
+}
+
 #undef PK_COPY_TILE
 #undef PK_WAIT_ALL_COPIES
 #undef PK_CODE
-
-    // ---- epilogue ----------------------------------------------------------
-    {
-        const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(l), __float_as_uint(l), false, false);
-        l = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
-    }
-    if (qrow < 0) return;
-    const float inv = l > 0.f ? 1.f / l : 0.f;
-    const int64_t obase = (static_cast<int64_t>(qrow) * a.Hq + head) * D;
-#pragma unroll
-    for (int b = 0; b < DB; ++b)
-#pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-            const int col = 32 * b + 8 * q4 + 4 * hlf;
-            const float x0 = o[b][4 * q4] * inv, x1 = o[b][4 * q4 + 1] * inv;
-            const float x2 = o[b][4 * q4 + 2] * inv, x3 = o[b][4 * q4 + 3] * inv;
-            if (a.out_f32) {
-                *reinterpret_cast<float4*>(static_cast<float*>(a.out) + obase + col) = make_float4(x0, x1, x2, x3);
-            } else {
-                *reinterpret_cast<uint2*>(static_cast<uint16_t*>(a.out) + obase + col) =
-                    make_uint2(pack_bf16x2(x0, x1), pack_bf16x2(x2, x3));
-            }
-        }
-}
 
 }  // namespace
 
@@ -419,8 +513,13 @@ int launch_prefill_bf16_pipe(const PrefillArgs& a, void* stream) {
         grid = static_cast<int64_t>(a.n_tiles) * a.Hq;
     }
     if (grid == 0) return 0;
-    hipLaunchKernelGGL(prefill_bf16_pipe_kernel, dim3(static_cast<unsigned>(grid)), dim3(256), 0,
-                       static_cast<hipStream_t>(stream), a);
+    static const bool pipelined = [] { const char* e = getenv("PK_PREFILL_PIPE"); return e && e[0] == '1'; }();
+    if (pipelined)
+        hipLaunchKernelGGL(prefill_bf16_pipe_kernel, dim3(static_cast<unsigned>(grid)), dim3(256), 0,
+                           static_cast<hipStream_t>(stream), a);
+    else
+        hipLaunchKernelGGL(prefill_bf16_dma_kernel, dim3(static_cast<unsigned>(grid)), dim3(256), 0,
+                           static_cast<hipStream_t>(stream), a);
     return static_cast<int>(hipGetLastError());
 }
 
