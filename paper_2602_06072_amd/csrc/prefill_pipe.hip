@@ -358,12 +358,14 @@ __global__ __launch_bounds__(256, 2) void prefill_bf16_dma_kernel(PrefillArgs a)
             bool rescale;
             qk_tile(s, qf, k_cur, off);
             const float alpha = softmax_tile<MASKED>(s, p, m, l, sl2, lazy, u.lo, hi_t, k_start, u.hlf, &rescale);
-            if (rescale) {                          // rare after the first tiles (wave-uniform)
+            (void)rescale;
+            // alpha is 1 unless the stored maximum was raised.  The multiply is unconditional on
+            // purpose: behind a branch the register allocator keeps the accumulators in two places
+            // and pays 64 register copies per tile on the common path.
 #pragma unroll
-                for (int b = 0; b < DB; ++b)
+            for (int b = 0; b < DB; ++b)
 #pragma unroll
-                    for (int e = 0; e < 16; ++e) o[b][e] *= alpha;
-            }
+                for (int e = 0; e < 16; ++e) o[b][e] *= alpha;
             pv_tile(o, p, v_cur, off);
         };
         if (code == 2) tile_step(std::false_type{});

@@ -274,6 +274,7 @@ void build_prefill_packed(const pk_plan& plan, const std::vector<int64_t>& q_sta
     constexpr int BM = kPrefillBM;
     SchedBuild sb;
     std::vector<QRow> rows;
+    std::vector<int32_t> tile_req;                 // request of a tile's first row
     rows.reserve(BM);
     for (const Group& g : plan.groups) {
         rows.clear();
@@ -281,17 +282,35 @@ void build_prefill_packed(const pk_plan& plan, const std::vector<int64_t>& q_sta
             for (int32_t x = 0; x < plan.q_lens[m.req]; ++x) {
                 rows.push_back({m.req, x});
                 if (rows.size() == BM) {
+                    tile_req.push_back(rows[0].req);
                     add_tile(plan, q_start, kv_start, rows.data(), BM, false, sb);
                     rows.clear();
                 }
             }
         }
-        if (!rows.empty())
+        if (!rows.empty()) {
+            tile_req.push_back(rows[0].req);
             add_tile(plan, q_start, kv_start, rows.data(), static_cast<int>(rows.size()), false, sb);
+        }
     }
     std::vector<int32_t> order(sb.n_kv.size());
     std::iota(order.begin(), order.end(), 0);
-    std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) { return sb.weight[x] > sb.weight[y]; });
+    // Launch order: request by request (the request whose heaviest tile is heaviest first), and
+    // inside a request the heaviest tile first.  Workgroups that run at the same time on one XCD
+    // then stream the same K/V rows, which keeps them in that XCD's L2; the many short tiles at
+    // the end of the list even out the tail.
+    std::vector<int64_t> req_weight(static_cast<size_t>(plan.n), 0);
+    for (size_t x = 0; x < tile_req.size(); ++x)
+        req_weight[static_cast<size_t>(tile_req[x])] = std::max(req_weight[static_cast<size_t>(tile_req[x])], sb.weight[x]);
+    std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) {
+        const int32_t rx = tile_req[static_cast<size_t>(x)], ry = tile_req[static_cast<size_t>(y)];
+        if (rx != ry) {
+            if (req_weight[static_cast<size_t>(rx)] != req_weight[static_cast<size_t>(ry)])
+                return req_weight[static_cast<size_t>(rx)] > req_weight[static_cast<size_t>(ry)];
+            return rx < ry;
+        }
+        return sb.weight[x] > sb.weight[y];
+    });
     emit_sched(sb, order, b, t.packed);
 }
 
