@@ -76,6 +76,19 @@ __device__ __forceinline__ void pv_tile(floatx16 (&o)[DB], const bf16x8 (&pf)[2]
                 o[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v_operand(vs, lo, kb, t, b), pf[kb][t], o[b], 0, 0, 0);
 }
 
+// -inf for the keys of a tile that a query row may not see (outside [lo, hi_t)).
+__device__ __forceinline__ void mask_tile(floatx16 (&s)[2], int lo, int hi_t, int k_start, int hlf) {
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int key = k_start + 32 * kb + 8 * (e >> 2) + 4 * hlf + (e & 3);
+            if (key < lo || key >= hi_t) s[kb][e] = -INFINITY;
+            // ties the masked value to this place, so that the selects stay behind the caller's branch
+            asm volatile("" : "+v"(s[kb][e]));
+        }
+}
+
 // Online softmax of one score tile with lazy rescaling (see prefill.hip for the argument).
 template <bool MASK>
 __device__ __forceinline__ float softmax_tile(floatx16 (&s)[2], bf16x8 (&pf)[2][2], float& m, float& l,
@@ -308,14 +321,13 @@ __device__ __forceinline__ void store_output(const PrefillArgs& a, const WorkUni
 #define PK_CODE(INFO) (((INFO) >> (8 + 2 * u.wave)) & 3)          /* 0 skip, 1 masked, 2 unmasked */
 
 // ---------------------------------------------------------------------------------------------
-// Kernel A (default): two workgroups per CU, two LDS stages per operand, plain tile loop.  The
-// copies of tile j+1 are requested before the math of tile j; the other workgroup of the CU
-// covers the wait at the end of the iteration.
+// Kernel A (default): two workgroups per CU (80 KiB of LDS each): three stages for K, two for V.
+// Iteration j requests K(j+2) and V(j+1) first, then runs QK(j) and the softmax, waits for the
+// copies of the PREVIOUS iteration (so every copy has one and a half to two iterations to land),
+// meets the other waves (barrier A: V(j) is complete), runs PV(j), and meets them again (barrier
+// B: the stages that the next iteration overwrites are no longer read).
 __global__ __launch_bounds__(256, 2) void prefill_bf16_dma_kernel(PrefillArgs a) {
-    __shared__ __align__(1024) unsigned char k_lds0[TILE_BYTES];
-    __shared__ __align__(1024) unsigned char k_lds1[TILE_BYTES];
-    __shared__ __align__(1024) unsigned char v_lds0[TILE_BYTES];
-    __shared__ __align__(1024) unsigned char v_lds1[TILE_BYTES];
+    __shared__ __align__(1024) unsigned char lds[5 * TILE_BYTES];   // K stages 0..2, V stages 3..4
     WorkUnit u;
     LaneOffsets off;
     bf16x8 qf[KS];
@@ -323,6 +335,10 @@ __global__ __launch_bounds__(256, 2) void prefill_bf16_dma_kernel(PrefillArgs a)
     const int n_kv = u.n_kv;
     const __attribute__((address_space(4))) int32_t* kvt_c =
         (const __attribute__((address_space(4))) int32_t*)(u.kvt);
+    auto entry = [&](int j, int& ks, int& info) {   // scalar loads; indices past the end are clamped
+        const int jj = j < n_kv ? j : n_kv - 1;
+        ks = kvt_c[2 * jj]; info = kvt_c[2 * jj + 1];
+    };
 
     floatx16 o[DB];
 #pragma unroll
@@ -333,52 +349,57 @@ __global__ __launch_bounds__(256, 2) void prefill_bf16_dma_kernel(PrefillArgs a)
     const float sl2 = a.scale * kLog2e;
     const float lazy = 8.0f / sl2;
 
-    int ks_cur = kvt_c[0], info_cur = kvt_c[1];
-    int ks_next = kvt_c[n_kv > 1 ? 2 : 0], info_next = kvt_c[n_kv > 1 ? 3 : 1];
-    PK_COPY_TILE(a.k, ks_cur, k_lds0);
-    PK_COPY_TILE(a.v, ks_cur, v_lds0);
+    // window of tile-list entries: e0 = tile j, e1 = tile j+1, e2 = tile j+2 (e3 is fetched for the next turn)
+    int e0s, e0i, e1s, e1i, e2s, e2i;
+    entry(0, e0s, e0i); entry(1, e1s, e1i); entry(2, e2s, e2i);
+    // prologue: K(0), K(1), V(0) (copies of tiles past the end are clamped duplicates into free stages)
+    PK_COPY_TILE(a.k, e0s, lds);
+    PK_COPY_TILE(a.k, e1s, lds + TILE_BYTES);
+    PK_COPY_TILE(a.v, e0s, lds + 3 * TILE_BYTES);
     PK_WAIT_ALL_COPIES();
     __syncthreads();
 
-    auto iteration = [&](int j, unsigned char* k_cur, unsigned char* v_cur, unsigned char* k_nxt, unsigned char* v_nxt) {
-        if (j + 1 < n_kv) {
-            PK_COPY_TILE(a.k, ks_next, k_nxt);
-            PK_COPY_TILE(a.v, ks_next, v_nxt);
+    int k_cur = 0, k_fill = 2 * TILE_BYTES;         // byte offsets of the K stage read now / filled now
+    int v_cur = 3 * TILE_BYTES, v_fill = 4 * TILE_BYTES;
+    for (int j = 0; j < n_kv; ++j) {
+        PK_COPY_TILE(a.k, e2s, lds + k_fill);
+        PK_COPY_TILE(a.v, e1s, lds + v_fill);
+        int e3s, e3i;
+        entry(j + 3, e3s, e3i);
+        const int code = PK_CODE(e0i);
+        const int k_start = e0s;
+        const int hi_t = min(u.hi, k_start + (e0i & 0xFF));   // keys past the tile's valid count are foreign
+        floatx16 s[2];
+        bf16x8 p[2][2];
+        float alpha = 1.f;
+        bool rescale = false;
+        if (code != 0) {
+            qk_tile(s, qf, lds + k_cur, off);
+            if (code == 1) {                          // diagonal or ragged tile: mask in place (unmasked tiles skip it)
+                mask_tile(s, u.lo, hi_t, k_start, u.hlf);
+            }
+            alpha = softmax_tile<false>(s, p, m, l, sl2, lazy, u.lo, hi_t, k_start, u.hlf, &rescale);
         }
-        const int jj = j + 2 < n_kv ? j + 2 : n_kv - 1;
-        const int ks_nn = kvt_c[2 * jj], info_nn = kvt_c[2 * jj + 1];      // scalar loads, used next iteration
-        const int code = PK_CODE(info_cur);
-        const int k_start = ks_cur;
-        const int hi_t = min(u.hi, k_start + (info_cur & 0xFF));   // keys past the tile's valid count are foreign
-        // the tile step exists twice so that unmasked tiles do not pay for the mask
-        auto tile_step = [&](auto masked_tag) {
-            constexpr bool MASKED = decltype(masked_tag)::value;
-            floatx16 s[2];
-            bf16x8 p[2][2];
-            bool rescale;
-            qk_tile(s, qf, k_cur, off);
-            const float alpha = softmax_tile<MASKED>(s, p, m, l, sl2, lazy, u.lo, hi_t, k_start, u.hlf, &rescale);
-            (void)rescale;
-            // alpha is 1 unless the stored maximum was raised.  The multiply is unconditional on
-            // purpose: behind a branch the register allocator keeps the accumulators in two places
-            // and pays 64 register copies per tile on the common path.
+        // Barrier A is taken with this iteration's eight copies still in flight (the compiler's
+        // own barrier would wait for all of them): everything requested earlier has landed.
+        asm volatile("s_waitcnt vmcnt(8)\n\ts_barrier" ::: "memory");
+        if (code != 0) {
+            if (rescale) {                            // rare: the stored maximum was raised
 #pragma unroll
-            for (int b = 0; b < DB; ++b)
+                for (int b = 0; b < DB; ++b)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) o[b][e] *= alpha;
-            pv_tile(o, p, v_cur, off);
-        };
-        if (code == 2) tile_step(std::false_type{});
-        else if (code == 1) tile_step(std::true_type{});
-        ks_cur = ks_next; info_cur = info_next;
-        ks_next = ks_nn; info_next = info_nn;
-        PK_WAIT_ALL_COPIES();
-        __syncthreads();
-    };
-    for (int j = 0; j < n_kv; j += 2) {
-        iteration(j, k_lds0, v_lds0, k_lds1, v_lds1);
-        if (j + 1 < n_kv) iteration(j + 1, k_lds1, v_lds1, k_lds0, v_lds0);
+                    for (int e = 0; e < 16; ++e) o[b][e] *= alpha;
+            }
+            pv_tile(o, p, lds + v_cur, off);
+        }
+        e0s = e1s; e0i = e1i; e1s = e2s; e1i = e2i; e2s = e3s; e2i = e3i;
+        k_cur = k_cur == 2 * TILE_BYTES ? 0 : k_cur + TILE_BYTES;
+        k_fill = k_fill == 2 * TILE_BYTES ? 0 : k_fill + TILE_BYTES;
+        const int tmp = v_cur; v_cur = v_fill; v_fill = tmp;
+        // barrier B: the stages overwritten by the next iteration's copies are no longer read
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
     }
+    PK_WAIT_ALL_COPIES();                          // nothing may still be writing LDS when the block ends
     store_output(a, u, o, l);
 }
 
