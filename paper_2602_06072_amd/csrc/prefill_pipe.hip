@@ -1,21 +1,18 @@
-// Packed prefill attention, bf16 MFMA, head dimension 128: software-pipelined
-// kernel (Sec. 3.1).  Same tables, same arithmetic and same operand scheme as
-// prefill.hip (S^T = K.Q^T, O^T += V^T.P^T with v_mfma_f32_32x32x16_bf16, one
-// wave per 32 query rows, key tiles of 64), but
-//   * K/V tiles go HBM/L2 -> LDS directly (buffer_load ... lds, 16 bytes per
-//     lane, no staging registers, hardware bounds check); rows are unpadded
-//     and the 16-byte chunks of a row are XOR-swizzled -- the swizzle is
-//     applied on the global side of the copy, so that both the K row reads
-//     (ds_read_b128) and the V transpose reads (ds_read_b64_tr_b16) are free
-//     of bank conflicts;
-//   * the loop is pipelined over key tiles: iteration j issues the score
-//     MFMAs of tile j+1, the PV MFMAs of tile j-1 and the softmax of tile j,
-//     which are independent, hand-interleaved so that the matrix pipe runs
-//     under the exponentials.  K is therefore staged two tiles ahead of the
-//     softmax and V zero tiles ahead; each has two LDS stages and there is
-//     one barrier per tile.
-#include <cstdlib>
-#include <type_traits>
+// Packed prefill attention, bf16 MFMA, head dimension 128 (Sec. 3.1).  Same tables, same
+// arithmetic and same operand scheme as prefill.hip (S^T = K.Q^T, O^T += V^T.P^T with
+// v_mfma_f32_32x32x16_bf16, one wave per 32 query rows, key tiles of 64), but
+//   * K/V tiles go HBM/L2 -> LDS directly (buffer_load ... lds, 16 bytes per lane, no staging
+//     registers, hardware bounds check); rows are unpadded and the 16-byte chunks of a row are
+//     XOR-swizzled -- the swizzle is applied on the global side of the copy, so that both the K
+//     row reads (ds_read_b128) and the V transpose reads (ds_read_b64_tr_b16) are free of bank
+//     conflicts;
+//   * a key tile is processed as two halves of 32 keys whose softmax steps are interleaved,
+//     slice by slice, with the MFMAs of the neighbouring phase, and the LDS operand reads run
+//     four MFMAs ahead in a ring of registers: matrix pipe, vector ALU and LDS overlap inside
+//     one wave, with no state crossing tiles except the accumulators;
+//   * copies are requested one tile ahead for V and two for K; one barrier per tile.
+
+#include <cstdint>
 
 #include "common.hip.h"
 #include "kernels.h"
@@ -41,22 +38,6 @@ struct LaneOffsets {
     int g[4];           // global byte offsets of this lane's four copy instructions
 };
 
-// S^T = K . Q^T for one tile of 64 keys: s[kb] holds keys 32kb..32kb+31.
-__device__ __forceinline__ void qk_tile(floatx16 (&s)[2], const bf16x8 (&qf)[KS],
-                                        const unsigned char* ks, const LaneOffsets& lo) {
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) s[kb][e] = 0.f;
-#pragma unroll
-    for (int st = 0; st < KS; ++st)
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-            const bf16x8 kf = *reinterpret_cast<const bf16x8*>(ks + lo.k[st] + kb * 32 * ROWB);
-            s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[st], s[kb], 0, 0, 0);
-        }
-}
-
 __device__ __forceinline__ bf16x8 v_operand(const unsigned char* vs, const LaneOffsets& lo, int kb, int t, int b) {
     const unsigned char* p = vs + (32 * kb + 16 * t) * ROWB;
     const bf16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)(p + lo.v1[b]));
@@ -64,165 +45,13 @@ __device__ __forceinline__ bf16x8 v_operand(const unsigned char* vs, const LaneO
     return __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
 }
 
-// O^T += V^T . P^T; MFMA (kb, t) contracts keys 32kb + 16t + {4hlf..+3} and {8+4hlf..+3}.
-__device__ __forceinline__ void pv_tile(floatx16 (&o)[DB], const bf16x8 (&pf)[2][2],
-                                        const unsigned char* vs, const LaneOffsets& lo) {
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-#pragma unroll
-            for (int b = 0; b < DB; ++b)
-                o[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v_operand(vs, lo, kb, t, b), pf[kb][t], o[b], 0, 0, 0);
-}
-
-// -inf for the keys of a tile that a query row may not see (outside [lo, hi_t)).
-__device__ __forceinline__ void mask_tile(floatx16 (&s)[2], int lo, int hi_t, int k_start, int hlf) {
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            const int key = k_start + 32 * kb + 8 * (e >> 2) + 4 * hlf + (e & 3);
-            if (key < lo || key >= hi_t) s[kb][e] = -INFINITY;
-            // ties the masked value to this place, so that the selects stay behind the caller's branch
-            asm volatile("" : "+v"(s[kb][e]));
-        }
-}
-
-// Online softmax of one score tile with lazy rescaling (see prefill.hip for the argument).
-template <bool MASK>
-__device__ __forceinline__ float softmax_tile(floatx16 (&s)[2], bf16x8 (&pf)[2][2], float& m, float& l,
-                                              float sl2, float lazy, int lo, int hi_t, int k_start,
-                                              int hlf, bool* rescale) {
-    if (MASK) {
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int key = k_start + 32 * kb + 8 * (e >> 2) + 4 * hlf + (e & 3);
-                if (key < lo || key >= hi_t) s[kb][e] = -INFINITY;
-            }
-    }
-    float mx = fmaxf(s[0][0], s[1][0]);
-#pragma unroll
-    for (int e = 1; e < 16; ++e) mx = fmaxf(fmaxf(mx, s[0][e]), s[1][e]);
-    {
-        const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
-        mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
-    }
-    const bool raise = __builtin_amdgcn_ballot_w64(mx > m + lazy || m == -INFINITY) != 0;
-    *rescale = raise;
-    const float m_new = raise ? fmaxf(m, mx) : m;
-    const float m_ref = (m_new == -INFINITY) ? 0.f : m_new;
-    const float alpha = __builtin_amdgcn_exp2f((m - m_ref) * sl2);   // m = -inf -> 0; unchanged m -> 1
-    m = m_new;
-    const float msl = m_ref * sl2;
-    float l0 = l * alpha, l1 = 0.f;
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            uint32_t w[4];
-#pragma unroll
-            for (int x = 0; x < 4; ++x) {
-                floatx2 pp;
-                pp[0] = __builtin_amdgcn_exp2f(fmaf(s[kb][8 * t + 2 * x], sl2, -msl));
-                pp[1] = __builtin_amdgcn_exp2f(fmaf(s[kb][8 * t + 2 * x + 1], sl2, -msl));
-                const bf16x2 pb = __builtin_convertvector(pp, bf16x2);
-                if (x & 1) l1 = __builtin_amdgcn_fdot2_f32_bf16(pb, bf16x2{(__bf16)1.0f, (__bf16)1.0f}, l1, false);
-                else l0 = __builtin_amdgcn_fdot2_f32_bf16(pb, bf16x2{(__bf16)1.0f, (__bf16)1.0f}, l0, false);
-                w[x] = __builtin_bit_cast(uint32_t, pb);
-            }
-            pf[kb][t] = __builtin_bit_cast(bf16x8, u32x4{w[0], w[1], w[2], w[3]});
-        }
-    l = l0 + l1;
-    return alpha;
-}
-
-// One steady-state iteration, hand-interleaved: each of the 16 score MFMAs of tile j+1 and of
-// the 16 PV MFMAs of tile j-1 is followed by a slice of the softmax of tile j (row maximum,
-// decision, then one exp/convert/sum slice per MFMA); LDS operand reads run PF MFMAs ahead.
-__device__ __forceinline__ float steady_step(floatx16 (&s_next)[2], floatx16 (&s_cur)[2], floatx16 (&o)[DB],
-                                             bf16x8 (&p)[2][2], const bf16x8 (&qf)[KS],
-                                             const unsigned char* ks, const unsigned char* vs,
-                                             const LaneOffsets& lo, float& m, float& l, float sl2,
-                                             float lazy, bool* rescale) {
-    constexpr int PF = 8;
-    auto kread = [&](int i) -> bf16x8 {            // MFMA i of the score phase: st = i / 2, kb = i % 2
-        return *reinterpret_cast<const bf16x8*>(ks + lo.k[i >> 1] + (i & 1) * 32 * ROWB);
-    };
-    auto vread = [&](int i) -> bf16x8 {            // MFMA i of the PV phase: (kb, t) = (i/8, (i/4)%2), b = i % 4
-        return v_operand(vs, lo, i >> 3, (i >> 2) & 1, i & 3);
-    };
-    float mx0 = -INFINITY, mx1 = -INFINITY, alpha = 1.f, msl = 0.f, l0 = 0.f, l1 = 0.f;
-    uint32_t pw[16];
-    auto slice = [&](int c) {
-        if (c < 4) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                mx0 = fmaxf(mx0, s_cur[0][4 * c + e]);
-                mx1 = fmaxf(mx1, s_cur[1][4 * c + e]);
-            }
-        } else if (c == 4) {
-            float mx = fmaxf(mx0, mx1);
-            const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
-            mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
-            const bool raise = __builtin_amdgcn_ballot_w64(mx > m + lazy || m == -INFINITY) != 0;
-            *rescale = raise;
-            const float m_new = raise ? fmaxf(m, mx) : m;
-            const float m_ref = (m_new == -INFINITY) ? 0.f : m_new;
-            alpha = __builtin_amdgcn_exp2f((m - m_ref) * sl2);
-            m = m_new;
-            msl = m_ref * sl2;
-            l0 = l * alpha;
-        } else if (c < 21) {
-            const int x = c - 5, kb = x >> 3, e = 2 * (x & 7);
-            floatx2 pp;
-            pp[0] = __builtin_amdgcn_exp2f(fmaf(s_cur[kb][e], sl2, -msl));
-            pp[1] = __builtin_amdgcn_exp2f(fmaf(s_cur[kb][e + 1], sl2, -msl));
-            const bf16x2 pb = __builtin_convertvector(pp, bf16x2);
-            if (x & 1) l1 = __builtin_amdgcn_fdot2_f32_bf16(pb, bf16x2{(__bf16)1.0f, (__bf16)1.0f}, l1, false);
-            else l0 = __builtin_amdgcn_fdot2_f32_bf16(pb, bf16x2{(__bf16)1.0f, (__bf16)1.0f}, l0, false);
-            pw[x] = __builtin_bit_cast(uint32_t, pb);
-        }
-    };
-
-    // PV of tile j-1 first: its P operands die as the new probabilities are produced
-    bf16x8 vf[PF + 1];
-#pragma unroll
-    for (int i = 0; i < PF; ++i) vf[i] = vread(i);
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        if (i + PF < 16) vf[(i + PF) % (PF + 1)] = vread(i + PF);
-        o[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i % (PF + 1)], p[i >> 3][(i >> 2) & 1], o[i & 3], 0, 0, 0);
-        slice(i);
-    }
-    const floatx16 zero = {};
-    bf16x8 kf[PF + 1];
-#pragma unroll
-    for (int i = 0; i < PF; ++i) kf[i] = kread(i);
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        if (i + PF < 16) kf[(i + PF) % (PF + 1)] = kread(i + PF);
-        s_next[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i % (PF + 1)], qf[i >> 1], i < 2 ? zero : s_next[i & 1], 0, 0, 0);
-        slice(16 + i);
-    }
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-            p[kb][t] = __builtin_bit_cast(bf16x8, u32x4{pw[8 * kb + 4 * t], pw[8 * kb + 4 * t + 1],
-                                                       pw[8 * kb + 4 * t + 2], pw[8 * kb + 4 * t + 3]});
-    l = l0 + l1;
-    return alpha;
-}
-
 // What a workgroup works on, and this lane's share of it.
 struct WorkUnit {
-    int head, kvh, n_kv, wave, lane, n, hlf;
+    int head, kvh, n_kv, n_active, wave, lane, n, hlf;   // n_active: key tiles before this wave's trailing skips
     int qrow, lo, hi;                  // this lane's query row (-1: padding) and its key range [lo, hi)
     const int32_t* kvt;                // key-tile list of the query tile: (first key row, info) pairs
     int64_t row_bytes;                 // bytes between consecutive K/V rows in global memory
+    uint32_t row_bytes32, total_rows32;  // the same, and the number of K/V rows, as 32-bit scalars
 };
 
 // Decodes the workgroup id, loads the row metadata and the Q operand, derives the lane offsets.
@@ -245,9 +74,12 @@ __device__ __forceinline__ bool setup(const PrefillArgs& a, WorkUnit& u, LaneOff
     const int tid = threadIdx.x;
     u.lane = tid & 63; u.n = u.lane & 31; u.hlf = u.lane >> 5;
     u.wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    u.n_active = u.n_kv - ((desc[3] >> (8 * u.wave)) & 0xFF);
     const int rr = tile * BM + u.wave * 32 + u.n;
     u.qrow = a.row_q[rr]; u.lo = a.row_lo[rr]; u.hi = a.row_hi[rr];
     u.row_bytes = static_cast<int64_t>(a.Hkv) * ROWB;
+    u.row_bytes32 = static_cast<uint32_t>(a.Hkv) * ROWB;
+    u.total_rows32 = static_cast<uint32_t>(a.total_kv_rows);
 
     const int fl = swz(u.n);
 #pragma unroll
@@ -303,31 +135,179 @@ __device__ __forceinline__ void store_output(const PrefillArgs& a, const WorkUni
         }
 }
 
-// copies the tile that starts at key row KSTART of `src` (a.k or a.v) into the LDS stage DST:
-// four 1-KiB wave instructions per wave, each lane fetching the chunk that belongs at its
-// (swizzled) LDS position; rows past the end of the array arrive as zeros
+// Copies the tile that starts at key row KSTART of `src` (a.k or a.v) into the LDS stage at byte
+// offset DST: four 1-KiB wave instructions per wave, each lane fetching the chunk that belongs at
+// its (swizzled) LDS position; rows past the end of the array arrive as zeros (the descriptor's
+// size is what is left of the array).  The copy is issued from inline assembly on purpose: the
+// compiler makes every later LDS read wait for all copies it knows of, also those into another
+// stage, which would serialise the pipeline.  The waits are explicit instead (vmcnt before the
+// barrier that publishes a stage).
+__device__ __forceinline__ void lds_copy_16(const u32x4& rsrc, uint32_t lds_addr, int voffset) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :: "s"(lds_addr), "v"(voffset), "s"(rsrc) : "memory", "m0");
+}
 #define PK_COPY_TILE(SRC, KSTART, DST)                                                       \
     {                                                                                        \
-        const int64_t ks_ = (KSTART);                                                        \
-        const int64_t left_ = (a.total_kv_rows - ks_) * u.row_bytes;                         \
-        const __amdgpu_buffer_rsrc_t rs_ = __builtin_amdgcn_make_buffer_rsrc(                \
-            const_cast<char*>(static_cast<const char*>(SRC)) + ks_ * u.row_bytes, 0,         \
-            static_cast<int>(left_ > 0x7FFFFFFFll ? 0x7FFFFFFFll : left_), 0x00020000);      \
+        const uint32_t ks_ = static_cast<uint32_t>(KSTART);       /* row counts fit 31 bits */ \
+        const uint64_t base_ = reinterpret_cast<uint64_t>(SRC) + static_cast<uint64_t>(ks_) * u.row_bytes32; \
+        const uint64_t left_ = static_cast<uint64_t>(u.total_rows32 - ks_) * u.row_bytes32;  \
+        u32x4 rs_;                                                                           \
+        rs_[0] = static_cast<uint32_t>(base_);                                               \
+        rs_[1] = static_cast<uint32_t>(base_ >> 32) & 0xFFFFu;    /* stride 0: raw buffer */  \
+        rs_[2] = static_cast<uint32_t>(left_ > 0x7FFFFFFFull ? 0x7FFFFFFFull : left_);       \
+        rs_[3] = 0x00020000u;                                                                \
         _Pragma("unroll") for (int q = 0; q < 4; ++q)                                        \
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(                                        \
-                rs_, (lds_void_ptr)((DST) + u.wave * 4096 + q * 1024), 16, off.g[q], 0, 0, 0); \
+            lds_copy_16(rs_, lds_base + (DST) + u.wave * 4096 + q * 1024, off.g[q]);         \
     }
 #define PK_WAIT_ALL_COPIES() __builtin_amdgcn_s_waitcnt(0x0F70)      /* vmcnt(0) */
 #define PK_CODE(INFO) (((INFO) >> (8 + 2 * u.wave)) & 3)          /* 0 skip, 1 masked, 2 unmasked */
 
 // ---------------------------------------------------------------------------------------------
-// Kernel A (default): two workgroups per CU (80 KiB of LDS each): three stages for K, two for V.
-// Iteration j requests K(j+2) and V(j+1) first, then runs QK(j) and the softmax, waits for the
-// copies of the PREVIOUS iteration (so every copy has one and a half to two iterations to land),
-// meets the other waves (barrier A: V(j) is complete), runs PV(j), and meets them again (barrier
-// B: the stages that the next iteration overwrites are no longer read).
+// Kernel A (default).  Two workgroups per CU (80 KiB of LDS each: three stages for K, two for V).
+// A key tile is handled as two halves of 32 keys, each with its own online-softmax step, so that
+// within one wave the matrix pipe and the vector ALU overlap without state that crosses tiles:
+//   phase 1   S0 = K(half 0) Q^T                                   (8 MFMAs)
+//   barrier   every copy requested one tile ago has landed; request V(j+1) and K(j+2)
+//   phase 2   S1 = K(half 1) Q^T      with the softmax of S0       (8 MFMAs + vector work)
+//   phase 3   O += V(half 0)^T P0^T   with the softmax of S1       (8 MFMAs + vector work)
+//   phase 4   O += V(half 1)^T P1^T                                (8 MFMAs)
+// The LDS operand reads of a phase are issued one phase ahead (the reads of phase 1 during phase 4
+// of the previous tile), into two register buffers of eight operands each.
+struct HalfSoftmax {
+    float mx, alpha, msl, l0, l1;
+    bool raise;
+    uint32_t pw[8];
+};
+
+// Slice C (0..7) of the softmax of one half tile (16 scores per lane): two slices of maxima and
+// the decision, then the eight pairs of exponentials spread over six slices.
+__device__ constexpr int slice_first_pair(int c) { return c == 2 ? 0 : c == 3 ? 2 : c == 4 ? 3 : c == 5 ? 4 : c == 6 ? 6 : 7; }
+__device__ constexpr int slice_pairs(int c) { return c < 2 ? 0 : (c == 2 || c == 5) ? 2 : 1; }
+
+template <int C>
+__device__ __forceinline__ void softmax_slice(const floatx16& s, HalfSoftmax& h, float& m, const float l,
+                                              float sl2, float lazy) {
+    if constexpr (C == 0) {
+        float mx = fmaxf(s[0], s[1]);
+#pragma unroll
+        for (int e = 2; e < 8; ++e) mx = fmaxf(mx, s[e]);
+        h.mx = mx;
+    } else if constexpr (C == 1) {
+        float mx = h.mx;
+#pragma unroll
+        for (int e = 8; e < 16; ++e) mx = fmaxf(mx, s[e]);
+        const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+        mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+        h.raise = __builtin_amdgcn_ballot_w64(mx > m + lazy || m == -INFINITY) != 0;
+        const float m_new = h.raise ? fmaxf(m, mx) : m;
+        const float m_ref = (m_new == -INFINITY) ? 0.f : m_new;
+        h.alpha = __builtin_amdgcn_exp2f((m - m_ref) * sl2);   // m = -inf -> 0; unchanged m -> 1
+        m = m_new;
+        h.msl = m_ref * sl2;
+        h.l0 = l * h.alpha;
+        h.l1 = 0.f;
+    } else {
+#pragma unroll
+        for (int q = slice_first_pair(C); q < slice_first_pair(C) + slice_pairs(C); ++q) {
+            floatx2 pp;
+            pp[0] = __builtin_amdgcn_exp2f(fmaf(s[2 * q], sl2, -h.msl));
+            pp[1] = __builtin_amdgcn_exp2f(fmaf(s[2 * q + 1], sl2, -h.msl));
+            const bf16x2 pb = __builtin_convertvector(pp, bf16x2);
+            if (q & 1) h.l1 = __builtin_amdgcn_fdot2_f32_bf16(pb, bf16x2{(__bf16)1.0f, (__bf16)1.0f}, h.l1, false);
+            else h.l0 = __builtin_amdgcn_fdot2_f32_bf16(pb, bf16x2{(__bf16)1.0f, (__bf16)1.0f}, h.l0, false);
+            h.pw[q] = __builtin_bit_cast(uint32_t, pb);
+        }
+    }
+}
+
+// The compiler is free to move the (side-effect free) softmax arithmetic and the MFMAs of a phase
+// apart again.  Two empty volatile asm statements per slice tie them together: the first makes the
+// slice's inputs depend on the point after MFMA i, the second makes the operand of MFMA i+1
+// depend on the point after the slice's results.
+template <int C>
+__device__ __forceinline__ void pin_slice_inputs(floatx16& acc, floatx16& s) {
+    if constexpr (C < 2) {
+        asm volatile("" : "+v"(acc));
+    } else if constexpr (slice_pairs(C) == 2) {
+        constexpr int e = 2 * slice_first_pair(C);
+        asm volatile("" : "+v"(acc), "+v"(s[e]), "+v"(s[e + 1]), "+v"(s[e + 2]), "+v"(s[e + 3]));
+    } else {
+        constexpr int e = 2 * slice_first_pair(C);
+        asm volatile("" : "+v"(acc), "+v"(s[e]), "+v"(s[e + 1]));
+    }
+}
+template <int C>
+__device__ __forceinline__ void pin_slice_outputs(bf16x8& next_operand, HalfSoftmax& h) {
+    if constexpr (C == 0) {
+        asm volatile("" : "+v"(next_operand), "+v"(h.mx));
+    } else if constexpr (C == 1) {
+        asm volatile("" : "+v"(next_operand), "+v"(h.msl), "+v"(h.l0), "+v"(h.alpha));
+    } else if constexpr (slice_pairs(C) == 2) {
+        constexpr int q = slice_first_pair(C);
+        asm volatile("" : "+v"(next_operand), "+v"(h.pw[q]), "+v"(h.pw[q + 1]), "+v"(h.l0), "+v"(h.l1));
+    } else {
+        constexpr int q = slice_first_pair(C);
+        asm volatile("" : "+v"(next_operand), "+v"(h.pw[q]), "+v"(h.l0), "+v"(h.l1));
+    }
+}
+
+// -inf for the keys of half `half` of a tile that a query row may not see (outside [lo, hi_t))
+__device__ __forceinline__ void mask_half(floatx16& s, int half, int lo, int hi_t, int k_start, int hlf) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+        const int key = k_start + 32 * half + 8 * (e >> 2) + 4 * hlf + (e & 3);
+        if (key < lo || key >= hi_t) s[e] = -INFINITY;
+        asm volatile("" : "+v"(s[e]));   // ties the selects to this place, behind the caller's branch
+    }
+}
+
+// operand x (0..7) of a half tile: K rows of contraction step x; V^T block (t, b) = (x / 4, x % 4)
+__device__ __forceinline__ bf16x8 k_operand(const unsigned char* ks, const LaneOffsets& lo, int half, int x) {
+    return *reinterpret_cast<const bf16x8*>(ks + lo.k[x] + half * 32 * ROWB);
+}
+__device__ __forceinline__ bf16x8 v_operand_x(const unsigned char* vs, const LaneOffsets& lo, int half, int x) {
+    return v_operand(vs, lo, half, x >> 2, x & 3);
+}
+// Operand stream of a tile: 0..7 K(half 0), 8..15 K(half 1), 16..23 V(half 0), 24..31 V(half 1),
+// 32..35 the first K operands of the next tile.  MFMA k takes ring[k % 4] and then refills that
+// slot with operand k + 4, so that every LDS read has four MFMAs (and their vector slices) to land.
+template <int K>
+__device__ __forceinline__ bf16x8 stream_operand(const unsigned char* k_cur, const unsigned char* v_cur,
+                                                 const unsigned char* k_next, const LaneOffsets& off) {
+    if constexpr (K < 16) return k_operand(k_cur, off, K >> 3, K & 7);
+    else if constexpr (K < 32) return v_operand_x(v_cur, off, (K - 16) >> 3, K & 7);
+    else return k_operand(k_next, off, 0, K - 32);
+}
+#define PK_REFILL(K0) ring[i & 3] = stream_operand<(K0) + i + 4>(lds + k_cur, lds + v_cur, lds + k_next, off)
+#define PK_SLICE(C, S, H, ACC, BODY)                                                          \
+    {                                                                                          \
+        constexpr int i = C;                                                                   \
+        BODY;                                                                                  \
+        pin_slice_inputs<C>(ACC, S);                                                           \
+        softmax_slice<C>(S, H, m, l, sl2, lazy);                                               \
+        pin_slice_outputs<C>(ring[(C + 1) & 3], H);                                            \
+    }
+// eight MFMAs (BODY, with accumulator ACC) interleaved with the softmax of the scores S
+#define PK_SLICES(S, H, ACC, BODY)                                                             \
+    PK_SLICE(0, S, H, ACC, BODY) PK_SLICE(1, S, H, ACC, BODY) PK_SLICE(2, S, H, ACC, BODY)       \
+    PK_SLICE(3, S, H, ACC, BODY) PK_SLICE(4, S, H, ACC, BODY) PK_SLICE(5, S, H, ACC, BODY)       \
+    PK_SLICE(6, S, H, ACC, BODY) PK_SLICE(7, S, H, ACC, BODY)
+
+#define PK_EIGHT(BODY)                                                                         \
+    {                                                                                          \
+        { constexpr int i = 0; BODY; __builtin_amdgcn_sched_barrier(0); }                      \
+        { constexpr int i = 1; BODY; __builtin_amdgcn_sched_barrier(0); }                      \
+        { constexpr int i = 2; BODY; __builtin_amdgcn_sched_barrier(0); }                      \
+        { constexpr int i = 3; BODY; __builtin_amdgcn_sched_barrier(0); }                      \
+        { constexpr int i = 4; BODY; __builtin_amdgcn_sched_barrier(0); }                      \
+        { constexpr int i = 5; BODY; __builtin_amdgcn_sched_barrier(0); }                      \
+        { constexpr int i = 6; BODY; __builtin_amdgcn_sched_barrier(0); }                      \
+        { constexpr int i = 7; BODY; __builtin_amdgcn_sched_barrier(0); }                      \
+    }
+
 __global__ __launch_bounds__(256, 2) void prefill_bf16_dma_kernel(PrefillArgs a) {
     __shared__ __align__(1024) unsigned char lds[5 * TILE_BYTES];   // K stages 0..2, V stages 3..4
+    const uint32_t lds_base = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_void_ptr)lds));
     WorkUnit u;
     LaneOffsets off;
     bf16x8 qf[KS];
@@ -353,174 +333,91 @@ __global__ __launch_bounds__(256, 2) void prefill_bf16_dma_kernel(PrefillArgs a)
     int e0s, e0i, e1s, e1i, e2s, e2i;
     entry(0, e0s, e0i); entry(1, e1s, e1i); entry(2, e2s, e2i);
     // prologue: K(0), K(1), V(0) (copies of tiles past the end are clamped duplicates into free stages)
-    PK_COPY_TILE(a.k, e0s, lds);
-    PK_COPY_TILE(a.k, e1s, lds + TILE_BYTES);
-    PK_COPY_TILE(a.v, e0s, lds + 3 * TILE_BYTES);
+    PK_COPY_TILE(a.k, e0s, 0);
+    PK_COPY_TILE(a.k, e1s, TILE_BYTES);
+    PK_COPY_TILE(a.v, e0s, 3 * TILE_BYTES);
     PK_WAIT_ALL_COPIES();
     __syncthreads();
 
-    int k_cur = 0, k_fill = 2 * TILE_BYTES;         // byte offsets of the K stage read now / filled now
+    bf16x8 ring[4];                                 // LDS operands of the next four MFMAs
+#pragma unroll
+    for (int x = 0; x < 4; ++x) ring[x] = k_operand(lds, off, 0, x);
+    int k_cur = 0, k_next = TILE_BYTES, k_fill = 2 * TILE_BYTES;   // K stage read now / next / filled now
     int v_cur = 3 * TILE_BYTES, v_fill = 4 * TILE_BYTES;
-    for (int j = 0; j < n_kv; ++j) {
-        PK_COPY_TILE(a.k, e2s, lds + k_fill);
-        PK_COPY_TILE(a.v, e1s, lds + v_fill);
-        int e3s, e3i;
-        entry(j + 3, e3s, e3i);
-        const int code = PK_CODE(e0i);
+    const floatx16 zero = {};
+    // After the barrier of tile j every wave is done with tile j-1, so the stages of K(j-1) and
+    // V(j-1) are refilled with V(j+1) and K(j+2); the copies requested one tile ago must have
+    // landed (only they matter: the compiler's own barrier would also wait for the LDS reads).
+#define PK_BARRIER_AND_REFILL()                                                               \
+    asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");                              \
+    PK_COPY_TILE(a.v, e1s, v_fill);                                                      \
+    PK_COPY_TILE(a.k, e2s, k_fill);                                                      \
+    int e3s, e3i;                                                                              \
+    entry(j + 3, e3s, e3i);
+#define PK_ROTATE()                                                                           \
+    e0s = e1s; e0i = e1i; e1s = e2s; e1i = e2i; e2s = e3s; e2i = e3i;                          \
+    { const int kc = k_cur; k_cur = k_next; k_next = k_fill; k_fill = kc; }                    \
+    { const int vc = v_cur; v_cur = v_fill; v_fill = vc; }
+
+    int j = 0;
+    for (; j < u.n_active; ++j) {
+        // a tile that this wave could skip inside its active range is computed as a masked one
+        const bool masked = PK_CODE(e0i) != 2;
         const int k_start = e0s;
         const int hi_t = min(u.hi, k_start + (e0i & 0xFF));   // keys past the tile's valid count are foreign
-        floatx16 s[2];
-        bf16x8 p[2][2];
-        float alpha = 1.f;
-        bool rescale = false;
-        if (code != 0) {
-            qk_tile(s, qf, lds + k_cur, off);
-            if (code == 1) {                          // diagonal or ragged tile: mask in place (unmasked tiles skip it)
-                mask_tile(s, u.lo, hi_t, k_start, u.hlf);
-            }
-            alpha = softmax_tile<false>(s, p, m, l, sl2, lazy, u.lo, hi_t, k_start, u.hlf, &rescale);
-        }
-        // Barrier A is taken with this iteration's eight copies still in flight (the compiler's
-        // own barrier would wait for all of them): everything requested earlier has landed.
-        asm volatile("s_waitcnt vmcnt(8)\n\ts_barrier" ::: "memory");
-        if (code != 0) {
-            if (rescale) {                            // rare: the stored maximum was raised
+        floatx16 s0, s1;
+        PK_EIGHT(s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[i & 3], qf[i], i == 0 ? zero : s0, 0, 0, 0);
+                 PK_REFILL(0));
+        PK_BARRIER_AND_REFILL();
+        HalfSoftmax h0, h1;
+        if (masked) mask_half(s0, 0, u.lo, hi_t, k_start, u.hlf);    // unmasked tiles skip the compares
+        PK_SLICES(s0, h0, s1, s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[i & 3], qf[i], i == 0 ? zero : s1, 0, 0, 0);
+                  PK_REFILL(8));
+        l = h0.l0 + h0.l1;
+        bf16x8 p0[2], p1[2];
 #pragma unroll
-                for (int b = 0; b < DB; ++b)
-#pragma unroll
-                    for (int e = 0; e < 16; ++e) o[b][e] *= alpha;
-            }
-            pv_tile(o, p, lds + v_cur, off);
-        }
-        e0s = e1s; e0i = e1i; e1s = e2s; e1i = e2i; e2s = e3s; e2i = e3i;
-        k_cur = k_cur == 2 * TILE_BYTES ? 0 : k_cur + TILE_BYTES;
-        k_fill = k_fill == 2 * TILE_BYTES ? 0 : k_fill + TILE_BYTES;
-        const int tmp = v_cur; v_cur = v_fill; v_fill = tmp;
-        // barrier B: the stages overwritten by the next iteration's copies are no longer read
-        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    }
-    PK_WAIT_ALL_COPIES();                          // nothing may still be writing LDS when the block ends
-    store_output(a, u, o, l);
-}
-
-// ---------------------------------------------------------------------------------------------
-// Kernel B (experimental, PK_PREFILL_PIPE=1): one workgroup per CU, four LDS stages per operand,
-// software-pipelined tile loop (see the head of this file).
-__global__ __launch_bounds__(256, 1) void prefill_bf16_pipe_kernel(PrefillArgs a) {
-    // four stages each for K and V (128 KiB: one workgroup per CU); separate arrays so that the
-    // copy into one stage is known not to alias the reads of another
-    __shared__ __align__(1024) unsigned char k_lds0[TILE_BYTES];
-    __shared__ __align__(1024) unsigned char k_lds1[TILE_BYTES];
-    __shared__ __align__(1024) unsigned char k_lds2[TILE_BYTES];
-    __shared__ __align__(1024) unsigned char k_lds3[TILE_BYTES];
-    __shared__ __align__(1024) unsigned char v_lds0[TILE_BYTES];
-    __shared__ __align__(1024) unsigned char v_lds1[TILE_BYTES];
-    __shared__ __align__(1024) unsigned char v_lds2[TILE_BYTES];
-    __shared__ __align__(1024) unsigned char v_lds3[TILE_BYTES];
-
-    WorkUnit u;
-    LaneOffsets off;
-    bf16x8 qf[KS];
-    if (!setup(a, u, off, qf)) return;
-    const int n_kv = u.n_kv, hlf = u.hlf, lo = u.lo, hi = u.hi;
-    const int32_t* kvt = u.kvt;
-
-    floatx16 o[DB];
-#pragma unroll
-    for (int b = 0; b < DB; ++b)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) o[b][e] = 0.f;
-    float m = -INFINITY, l = 0.f;
-    const float sl2 = a.scale * kLog2e;
-    const float lazy = 8.0f / sl2;
-
-    // Entries (first key row, info) of the tile list are needed as scalars (copy descriptors,
-    // wave codes).  They are read through the constant address space (scalar loads, which do not
-    // share a counter with the tile copies) one iteration ahead of their use, and kept in a window:
-    // es[x], ei[x] describe tile j + x.
-    const __attribute__((address_space(4))) int32_t* kvt_c =
-        (const __attribute__((address_space(4))) int32_t*)(kvt);
-    auto entry = [&](int j, int& ks, int& info) {
-        const int jj = j < n_kv ? j : n_kv - 1;
-        ks = kvt_c[2 * jj]; info = kvt_c[2 * jj + 1];
-    };
-    int es[6], ei[6];
-#pragma unroll
-    for (int x = 0; x < 6; ++x) entry(x, es[x], ei[x]);
-
-    // ---- prologue: K(0..3), V(0), V(1) into LDS, scores of tile 0 -------------
-    // (tile indices past the end are clamped: such copies land in stages nobody reads)
-    PK_COPY_TILE(a.k, es[0], k_lds0);
-    PK_COPY_TILE(a.k, es[1], k_lds1);
-    PK_COPY_TILE(a.k, es[2], k_lds2);
-    PK_COPY_TILE(a.k, es[3], k_lds3);
-    PK_COPY_TILE(a.v, es[0], v_lds0);
-    PK_COPY_TILE(a.v, es[1], v_lds1);
-    PK_WAIT_ALL_COPIES();
-    __syncthreads();
-    floatx16 s_a[2], s_b[2];
-    bf16x8 p_prev[2][2];
-    int c_prev = 0, c_cur = PK_CODE(ei[0]);
-    if (c_cur) qk_tile(s_a, qf, k_lds0, off);
-    __syncthreads();                               // stage 0 of K is free again
-
-    // Iteration j: s_c holds the scores of tile j, s_n receives those of tile j+1.
-    // In LDS: K(j+1) in k_next, V(j-1) in v_prev.  Copied now: K(j+4) -> k_free (held K(j)),
-    // V(j+2) -> v_free (held V(j-2)).  At the end K(j+2) and V(j) must have landed: they were
-    // requested two iterations ago, so the 16 copy instructions of this and of the previous
-    // iteration may remain in flight.
-    auto iteration = [&](int j, floatx16 (&s_c)[2], floatx16 (&s_n)[2], unsigned char* k_next,
-                         unsigned char* k_free, unsigned char* v_prev, unsigned char* v_free) {
-        PK_COPY_TILE(a.k, es[4], k_free);
-        PK_COPY_TILE(a.v, es[2], v_free);
-        int ns, ni;
-        entry(j + 6, ns, ni);
-        const int c_next = (j + 1 < n_kv) ? PK_CODE(ei[1]) : 0;
-        const int k_start = es[0];
-        const int hi_t = min(hi, k_start + (ei[0] & 0xFF));   // keys past the tile's valid count are foreign
-        bool rescale = false;
-        float alpha = 1.f;
-        if (c_next != 0 && c_prev != 0 && c_cur == 2) {
-            alpha = steady_step(s_n, s_c, o, p_prev, qf, k_next, v_prev, off, m, l, sl2, lazy, &rescale);
-        } else {
-            if (c_next != 0) qk_tile(s_n, qf, k_next, off);
-            if (c_prev != 0) pv_tile(o, p_prev, v_prev, off);
-            if (c_cur == 2) alpha = softmax_tile<false>(s_c, p_prev, m, l, sl2, lazy, lo, hi_t, k_start, hlf, &rescale);
-            else if (c_cur == 1) alpha = softmax_tile<true>(s_c, p_prev, m, l, sl2, lazy, lo, hi_t, k_start, hlf, &rescale);
-        }
-        if (rescale) {                              // rare after the first tiles (wave-uniform)
+        for (int t = 0; t < 2; ++t)
+            p0[t] = __builtin_bit_cast(bf16x8, u32x4{h0.pw[4 * t], h0.pw[4 * t + 1], h0.pw[4 * t + 2], h0.pw[4 * t + 3]});
+        if (h0.raise) {                              // rare: the stored maximum was raised
 #pragma unroll
             for (int b = 0; b < DB; ++b)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) o[b][e] *= alpha;
+                for (int e = 0; e < 16; ++e) o[b][e] *= h0.alpha;
         }
-        c_prev = c_cur;                             // p_prev now holds the probabilities of tile j
-        c_cur = c_next;
+        if (masked) mask_half(s1, 1, u.lo, hi_t, k_start, u.hlf);
+        PK_SLICES(s1, h1, o[i & 3], o[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[i & 3], p0[i >> 2], o[i & 3], 0, 0, 0);
+                  PK_REFILL(16));
+        l = h1.l0 + h1.l1;
 #pragma unroll
-        for (int x = 0; x < 5; ++x) { es[x] = es[x + 1]; ei[x] = ei[x + 1]; }
-        es[5] = ns; ei[5] = ni;
-        // Barrier with copies still in flight: the compiler's own barrier would first wait for
-        // every outstanding memory operation, so the wait and the barrier are spelled out.  All
-        // copies are bounds-checked buffer loads; this wave's LDS reads of the stages that are
-        // overwritten next were consumed by MFMAs above.
-        asm volatile("s_waitcnt vmcnt(16)\n\ts_barrier" ::: "memory");
-    };
-    for (int j = 0; j < n_kv; j += 4) {
-        iteration(j, s_a, s_b, k_lds1, k_lds0, v_lds3, v_lds2);
-        if (j + 1 < n_kv) iteration(j + 1, s_b, s_a, k_lds2, k_lds1, v_lds0, v_lds3);
-        if (j + 2 < n_kv) iteration(j + 2, s_a, s_b, k_lds3, k_lds2, v_lds1, v_lds0);
-        if (j + 3 < n_kv) iteration(j + 3, s_b, s_a, k_lds0, k_lds3, v_lds2, v_lds1);
+        for (int t = 0; t < 2; ++t)
+            p1[t] = __builtin_bit_cast(bf16x8, u32x4{h1.pw[4 * t], h1.pw[4 * t + 1], h1.pw[4 * t + 2], h1.pw[4 * t + 3]});
+        if (h1.raise) {
+#pragma unroll
+            for (int b = 0; b < DB; ++b)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) o[b][e] *= h1.alpha;
+        }
+        // phase 4; its last refills are the first operands of the next tile (K(j+1) landed before the barrier)
+        PK_EIGHT(o[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[i & 3], p1[i >> 2], o[i & 3], 0, 0, 0);
+                 PK_REFILL(24));
+        PK_ROTATE();
+    }
+    // trailing tiles that this wave skips: it only takes part in the barriers and in the copies
+    for (; j < n_kv; ++j) {
+        PK_BARRIER_AND_REFILL();
+        PK_ROTATE();
     }
     PK_WAIT_ALL_COPIES();                          // nothing may still be writing LDS when the block ends
-    // drain: PV of the last tile
-    if (c_prev != 0) {
-        const int last = (n_kv - 1) & 3;
-        pv_tile(o, p_prev, last == 0 ? v_lds0 : last == 1 ? v_lds1 : last == 2 ? v_lds2 : v_lds3, off);
-    }
     store_output(a, u, o, l);
 }
 
 #undef PK_COPY_TILE
+#undef PK_BARRIER_AND_REFILL
+#undef PK_ROTATE
+#undef PK_SLICE
+#undef PK_SLICES
+#undef PK_EIGHT
+#undef PK_REFILL
 #undef PK_WAIT_ALL_COPIES
 #undef PK_CODE
 
@@ -536,13 +433,8 @@ int launch_prefill_bf16_pipe(const PrefillArgs& a, void* stream) {
         grid = static_cast<int64_t>(a.n_tiles) * a.Hq;
     }
     if (grid == 0) return 0;
-    static const bool pipelined = [] { const char* e = getenv("PK_PREFILL_PIPE"); return e && e[0] == '1'; }();
-    if (pipelined)
-        hipLaunchKernelGGL(prefill_bf16_pipe_kernel, dim3(static_cast<unsigned>(grid)), dim3(256), 0,
-                           static_cast<hipStream_t>(stream), a);
-    else
-        hipLaunchKernelGGL(prefill_bf16_dma_kernel, dim3(static_cast<unsigned>(grid)), dim3(256), 0,
-                           static_cast<hipStream_t>(stream), a);
+    hipLaunchKernelGGL(prefill_bf16_dma_kernel, dim3(static_cast<unsigned>(grid)), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), a);
     return static_cast<int>(hipGetLastError());
 }
 

@@ -255,7 +255,18 @@ void emit_sched(const SchedBuild& sb, const std::vector<int32_t>& order, Builder
         desc.push_back(static_cast<int32_t>(kv.size() / 2));
         desc.push_back(sb.n_kv[idx]);
         desc.push_back(sb.n_rows[idx]);
-        desc.push_back(0);
+        // per wave (8 bits each, saturating): how many key tiles at the END of the list the wave skips
+        int32_t trailing = 0;
+        for (int w = 0; w < 4; ++w) {
+            int32_t cnt = 0;
+            for (int32_t e = sb.n_kv[idx] - 1; e >= 0 && cnt < 255; --e) {
+                const int32_t info = sb.kv[2 * (static_cast<size_t>(sb.kv_first[idx]) + e) + 1];
+                if (((info >> (8 + 2 * w)) & 3) != 0) break;
+                ++cnt;
+            }
+            trailing |= cnt << (8 * w);
+        }
+        desc.push_back(trailing);
         rq.insert(rq.end(), sb.row_q.begin() + idx * BM, sb.row_q.begin() + (idx + 1) * BM);
         rlo.insert(rlo.end(), sb.row_lo.begin() + idx * BM, sb.row_lo.begin() + (idx + 1) * BM);
         rhi.insert(rhi.end(), sb.row_hi.begin() + idx * BM, sb.row_hi.begin() + (idx + 1) * BM);
