@@ -135,6 +135,40 @@ __device__ __forceinline__ void store_output(const PrefillArgs& a, const WorkUni
         }
 }
 
+// bf16 output through LDS, so that every row leaves as whole 16-byte pieces (four rows of 256
+// bytes per store instruction) instead of 8-byte pieces of 32 different rows.  The wave uses two
+// 4-KiB pieces of LDS that belong to it alone (rows 0..15 in qa, rows 16..31 in qb); the 16-byte
+// chunks of a row are XOR-swizzled with the row number, which keeps both sides off bank conflicts.
+__device__ __forceinline__ void store_output_bf16(const PrefillArgs& a, const WorkUnit& u, const floatx16 (&o)[DB],
+                                                  float l, unsigned char* qa, unsigned char* qb) {
+    {
+        const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(l), __float_as_uint(l), false, false);
+        l = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
+    }
+    const float inv = l > 0.f ? 1.f / l : 0.f;
+    const int rr = u.n & 15;
+    unsigned char* wrow = (u.n < 16 ? qa : qb) + rr * ROWB + 8 * u.hlf;
+#pragma unroll
+    for (int b = 0; b < DB; ++b)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {       // columns 32b + 8q4 + 4hlf .. +3: chunk 4b + q4, half hlf
+            const float x0 = o[b][4 * q4] * inv, x1 = o[b][4 * q4 + 1] * inv;
+            const float x2 = o[b][4 * q4 + 2] * inv, x3 = o[b][4 * q4 + 3] * inv;
+            *reinterpret_cast<uint2*>(wrow + (((4 * b + q4) ^ rr) << 4)) =
+                make_uint2(pack_bf16x2(x0, x1), pack_bf16x2(x2, x3));
+        }
+    const int chunk = u.lane & 15;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        const int row = 4 * k + (u.lane >> 4), r2 = row & 15;
+        const u32x4 v = *reinterpret_cast<const u32x4*>((row < 16 ? qa : qb) + r2 * ROWB + ((chunk ^ r2) << 4));
+        const int qrow = __shfl(u.qrow, row, 64);
+        if (qrow >= 0)
+            *reinterpret_cast<u32x4*>(static_cast<uint16_t*>(a.out) +
+                                      (static_cast<int64_t>(qrow) * a.Hq + u.head) * D + 8 * chunk) = v;
+    }
+}
+
 // Copies the tile that starts at key row KSTART of `src` (a.k or a.v) into the LDS stage at byte
 // offset DST: four 1-KiB wave instructions per wave, each lane fetching the chunk that belongs at
 // its (swizzled) LDS position; rows past the end of the array arrive as zeros (the descriptor's
@@ -144,7 +178,8 @@ __device__ __forceinline__ void store_output(const PrefillArgs& a, const WorkUni
 // barrier that publishes a stage).
 __device__ __forceinline__ void lds_copy_16(const u32x4& rsrc, uint32_t lds_addr, int voffset) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
-                 :: "s"(lds_addr), "v"(voffset), "s"(rsrc) : "memory", "m0");
+                 :: "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(voffset), "s"(rsrc)
+                 : "memory");                       // M0 has no other user in this file
 }
 #define PK_COPY_TILE(SRC, KSTART, DST)                                                       \
     {                                                                                        \
@@ -350,8 +385,8 @@ __global__ __launch_bounds__(256, 2) void prefill_bf16_dma_kernel(PrefillArgs a)
     // landed (only they matter: the compiler's own barrier would also wait for the LDS reads).
 #define PK_BARRIER_AND_REFILL()                                                               \
     asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");                              \
-    PK_COPY_TILE(a.v, e1s, v_fill);                                                      \
-    PK_COPY_TILE(a.k, e2s, k_fill);                                                      \
+    if (j + 1 < n_kv) PK_COPY_TILE(a.v, e1s, v_fill);                                          \
+    if (j + 2 < n_kv) PK_COPY_TILE(a.k, e2s, k_fill);                                          \
     int e3s, e3i;                                                                              \
     entry(j + 3, e3s, e3i);
 #define PK_ROTATE()                                                                           \
@@ -407,8 +442,12 @@ __global__ __launch_bounds__(256, 2) void prefill_bf16_dma_kernel(PrefillArgs a)
         PK_BARRIER_AND_REFILL();
         PK_ROTATE();
     }
-    PK_WAIT_ALL_COPIES();                          // nothing may still be writing LDS when the block ends
-    store_output(a, u, o, l);
+    // After the last barrier nobody reads or fills the two stages that would have taken tiles
+    // n_kv and n_kv + 1 (after the final rotation: k_next and v_cur), and a wave's copies only
+    // ever touch its own quarter of a stage: those two quarters stage this wave's output.
+    PK_WAIT_ALL_COPIES();                          // (none is outstanding here; kept as a guard)
+    if (a.out_f32) store_output(a, u, o, l);
+    else store_output_bf16(a, u, o, l, lds + k_next + u.wave * 4096, lds + v_cur + u.wave * 4096);
 }
 
 #undef PK_COPY_TILE
