@@ -269,7 +269,7 @@ def main():
         "roofline": {"bound": "mfma", "achieved": r2["kernel_tflops"], "peak": MFMA_BF16_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": r2["kernel_tflops"] / MFMA_BF16_PEAK_TFLOPS,
                      "traffic": profiled_traffic("prefill_cfg2_packed") if args.seed == 0 else None,
-                     "kernel": "prefill_bf16_kernel<128>", "kernel_ms": r2["kernel_ms"]},
+                     "kernel": "prefill_bf16_dma_kernel", "kernel_ms": r2["kernel_ms"]},
     }
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline(w2)

@@ -13,7 +13,8 @@
 // operand layout of the second.  K/V tiles are staged through LDS (double
 // buffered, one barrier per tile); global loads of tile j+1 are issued before
 // the math of tile j.  MFMA-bound: 4*D flops per (query, key) pair.
-#include <cstdlib>
+// This staged kernel serves head dimension 64; head dimension 128 runs the
+// direct-to-LDS kernel of prefill_pipe.hip (same tables, same arithmetic).
 
 #include "common.hip.h"
 #include "kernels.h"
@@ -310,9 +311,7 @@ int launch_prefill_bf16_pipe(const PrefillArgs& a, void* stream);
 
 int launch_prefill_bf16(const PrefillArgs& a, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
-    static const bool use_staged = [] { const char* e = getenv("PK_PREFILL_STAGED"); return e && e[0] == '1'; }();
-    if (a.d == 128 && !use_staged) return launch_prefill_bf16_pipe(a, stream);
-    if (a.d == 128) return launch_p<128>(a, st);
+    if (a.d == 128) return launch_prefill_bf16_pipe(a, stream);   // direct-to-LDS kernel (prefill_pipe.hip)
     if (a.d == 64) return launch_p<64>(a, st);
     return static_cast<int>(hipErrorInvalidValue);
 }
