@@ -219,22 +219,30 @@ struct HalfSoftmax {
 __device__ constexpr int slice_first_pair(int c) { return c == 2 ? 0 : c == 3 ? 2 : c == 4 ? 3 : c == 5 ? 4 : c == 6 ? 6 : 7; }
 __device__ constexpr int slice_pairs(int c) { return c < 2 ? 0 : (c == 2 || c == 5) ? 2 : 1; }
 
+// max without the canonicalising self-maximum that fmaxf() costs per operand (scores are never NaN;
+// -inf is ordinary here).  Not volatile: the compiler schedules these like any arithmetic.
+__device__ __forceinline__ float max3f(float a, float b, float c) {
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+__device__ __forceinline__ float max2f(float a, float b) {
+    float r;
+    asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+
 template <int C>
 __device__ __forceinline__ void softmax_slice(const floatx16& s, HalfSoftmax& h, float& m, const float l,
                                               float sl2, float lazy) {
     if constexpr (C == 0) {
-        float mx = fmaxf(s[0], s[1]);
-#pragma unroll
-        for (int e = 2; e < 8; ++e) mx = fmaxf(mx, s[e]);
-        h.mx = mx;
+        h.mx = max3f(max3f(max3f(max2f(s[0], s[1]), s[2], s[3]), s[4], s[5]), s[6], s[7]);
     } else if constexpr (C == 1) {
-        float mx = h.mx;
-#pragma unroll
-        for (int e = 8; e < 16; ++e) mx = fmaxf(mx, s[e]);
+        float mx = max3f(max3f(max3f(max3f(h.mx, s[8], s[9]), s[10], s[11]), s[12], s[13]), s[14], s[15]);
         const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
-        mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+        mx = max2f(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
         h.raise = __builtin_amdgcn_ballot_w64(mx > m + lazy || m == -INFINITY) != 0;
-        const float m_new = h.raise ? fmaxf(m, mx) : m;
+        const float m_new = h.raise ? max2f(m, mx) : m;
         const float m_ref = (m_new == -INFINITY) ? 0.f : m_new;
         h.alpha = __builtin_amdgcn_exp2f((m - m_ref) * sl2);   // m = -inf -> 0; unchanged m -> 1
         m = m_new;
@@ -257,19 +265,13 @@ __device__ __forceinline__ void softmax_slice(const floatx16& s, HalfSoftmax& h,
 
 // The compiler is free to move the (side-effect free) softmax arithmetic and the MFMAs of a phase
 // apart again.  Two empty volatile asm statements per slice tie them together: the first makes the
-// slice's inputs depend on the point after MFMA i, the second makes the operand of MFMA i+1
-// depend on the point after the slice's results.
+// slice's inputs depend on the point after MFMA i (for the exponential slices through the
+// subtrahend they all share), the second makes the operand of MFMA i+1 depend on the point after
+// the slice's results.
 template <int C>
-__device__ __forceinline__ void pin_slice_inputs(floatx16& acc, floatx16& s) {
-    if constexpr (C < 2) {
-        asm volatile("" : "+v"(acc));
-    } else if constexpr (slice_pairs(C) == 2) {
-        constexpr int e = 2 * slice_first_pair(C);
-        asm volatile("" : "+v"(acc), "+v"(s[e]), "+v"(s[e + 1]), "+v"(s[e + 2]), "+v"(s[e + 3]));
-    } else {
-        constexpr int e = 2 * slice_first_pair(C);
-        asm volatile("" : "+v"(acc), "+v"(s[e]), "+v"(s[e + 1]));
-    }
+__device__ __forceinline__ void pin_slice_inputs(floatx16& acc, HalfSoftmax& h) {
+    if constexpr (C < 2) asm volatile("" : "+v"(acc));
+    else asm volatile("" : "+v"(acc), "+v"(h.msl));
 }
 template <int C>
 __device__ __forceinline__ void pin_slice_outputs(bf16x8& next_operand, HalfSoftmax& h) {
@@ -318,7 +320,7 @@ __device__ __forceinline__ bf16x8 stream_operand(const unsigned char* k_cur, con
     {                                                                                          \
         constexpr int i = C;                                                                   \
         BODY;                                                                                  \
-        pin_slice_inputs<C>(ACC, S);                                                           \
+        pin_slice_inputs<C>(ACC, H);                                                           \
         softmax_slice<C>(S, H, m, l, sl2, lazy);                                               \
         pin_slice_outputs<C>(ring[(C + 1) & 3], H);                                            \
     }
