@@ -186,10 +186,10 @@ __device__ __forceinline__ void lds_copy_16(const u32x4& rsrc, uint32_t lds_addr
         const uint32_t ks_ = static_cast<uint32_t>(KSTART);       /* row counts fit 31 bits */ \
         const uint64_t base_ = reinterpret_cast<uint64_t>(SRC) + static_cast<uint64_t>(ks_) * u.row_bytes32; \
         const uint64_t left_ = static_cast<uint64_t>(u.total_rows32 - ks_) * u.row_bytes32;  \
-        u32x4 rs_;                                                                           \
-        rs_[0] = static_cast<uint32_t>(base_);                                               \
-        rs_[1] = static_cast<uint32_t>(base_ >> 32) & 0xFFFFu;    /* stride 0: raw buffer */  \
-        rs_[2] = static_cast<uint32_t>(left_ > 0x7FFFFFFFull ? 0x7FFFFFFFull : left_);       \
+        u32x4 rs_;                                /* wave-uniform by construction: keep it in SGPRs */ \
+        rs_[0] = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(base_));               \
+        rs_[1] = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(base_ >> 32) & 0xFFFFu);  /* stride 0: raw buffer */ \
+        rs_[2] = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(left_ > 0x7FFFFFFFull ? 0x7FFFFFFFull : left_)); \
         rs_[3] = 0x00020000u;                                                                \
         _Pragma("unroll") for (int q = 0; q < 4; ++q)                                        \
             lds_copy_16(rs_, lds_base + (DST) + u.wave * 4096 + q * 1024, off.g[q]);         \
