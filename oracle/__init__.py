@@ -13,5 +13,10 @@ Modules:
   planner   -- Alg. 1 (greedy length-balanced grouping, prefix-first layout)
                restated from the paper; pinned.  The values of the headroom
                delta and of M_max are "parity unpinned": the paper prints no
-               number for either.
+               number for either.  Also the decode-step evolution rules: group
+               loads after t steps, the drift and the regrouping trigger of
+               Eq. 4 (pinned by hand-worked examples and a brute force of the
+               definition); the cadence the paper mentions for its own
+               workloads (every 20-40 steps) is "parity unpinned".
+  paged.append_step -- the headroom slot a generated token goes to (Sec. 3.2); pinned.
 """

@@ -43,3 +43,15 @@ def group_buffer(pages, block_table, page_size, members, total_tokens, fill):
             buf[poff:poff + lp] = full[:lp]
         buf[soff:soff + lq] = full[lp:lp + lq]
     return buf
+
+
+def append_step(buf, members, step, new_rows):
+    """The token generated at decode step `step` (0-based) goes into the headroom of its request's
+    suffix: row suffix_off + L_Q + step of the group buffer (Sec. 3.2, M(Q_i) = L_Q + delta).
+
+    buf: [total_tokens, Hkv, d] of one group, modified in place; new_rows: [n, Hkv, d] indexed by
+    request; members as in O_g.  The caller keeps step < delta.
+    """
+    for (req, _poff, _lp, soff, lq) in members:
+        buf[soff + lq + step] = new_rows[req]
+    return buf

@@ -152,3 +152,27 @@ def make_plan(kv_lens: Sequence[int], q_lens: Optional[Sequence[int]] = None,
         base = -(-(base + delta) // GROUP_ALIGN) * GROUP_ALIGN
         groups.append(g)
     return Plan(n, C, int(headroom), groups, base)
+
+
+# ---- decode-step evolution (Sec. 3.1 "Adaptive Grouping", Eq. 4; Sec. 3.2 headroom) ----------
+def group_loads_after(plan: Plan, t: int) -> List[int]:
+    """L(S_g) after t decode steps: every member of a group has produced t new tokens, each of
+    which is a unique suffix token of that group (prefixes do not grow)."""
+    return [g.load + t * len(g.members) for g in plan.groups]
+
+
+def drift_after(plan: Plan, t: int) -> int:
+    """Delta L = |max_g L(S_g) - min_g L(S_g)| with the loads as they stand after t steps."""
+    loads = group_loads_after(plan, t)
+    return max(loads) - min(loads) if loads else 0
+
+
+def regroup_due(plan: Plan, t: int) -> bool:
+    """Eq. 4: regroup once t * Delta L >= C / 2, t counted from the last (re)grouping."""
+    return 2 * t * drift_after(plan, t) >= plan.token_budget
+
+
+def headroom_exhausted(plan: Plan, t: int) -> bool:
+    """After t appended tokens per request a further one has no slot left (Sec. 3.2: every suffix
+    is allocated L_Q + delta tokens)."""
+    return t >= plan.headroom

@@ -175,9 +175,11 @@ __device__ __forceinline__ void store_output_bf16(const PrefillArgs& a, const Wo
 // size is what is left of the array).  The copy is issued from inline assembly on purpose: the
 // compiler makes every later LDS read wait for all copies it knows of, also those into another
 // stage, which would serialise the pipeline.  The waits are explicit instead (vmcnt before the
-// barrier that publishes a stage).
+// barrier that publishes a stage).  The compiler does not look into the assembly for hazards: a
+// descriptor word that a VALU instruction (v_readfirstlane) wrote just before needs five wait
+// states before a memory instruction may read it, hence the s_nop 4 (it also covers M0).
 __device__ __forceinline__ void lds_copy_16(const u32x4& rsrc, uint32_t lds_addr, int voffset) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 4\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
                  :: "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(voffset), "s"(rsrc)
                  : "memory");                       // M0 has no other user in this file
 }
