@@ -118,9 +118,7 @@ int64_t pk_plan_serialize(const pk_plan* plan, int32_t* out, int64_t cap);
  *       kappa(g, j) = 4g + j for j < 4, 16 + 4g + (j-4) otherwise.
  *   (This is the operand order of the 16x16x32 bf16 MFMA, so the decode
  *   kernel streams tiles with fully coalesced 16-byte loads.)  Token slots
- *   that hold no valid token (headroom, alignment) are zero inside tiles
- *   that hold at least one valid token; tiles without valid tokens are not
- *   written.
+ *   that hold no valid token (headroom, alignment) are written as zeros.
  *   PK_F32 layout: K as [Hkv][buf_tokens][d] floats, then V likewise.
  *
  * pk_workspace_bytes: bytes of the workspace that carries the plan's device
@@ -193,6 +191,43 @@ int pk_packed_decode_attn(pk_plan* plan, const void* q, const void* kv_buf,
                           void* out, float scale, int Hq, int Hkv, int d,
                           int dtype, int out_dtype,
                           void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
+ * Decoding over several steps with one plan (Sec. 3.2: every suffix is
+ * allocated L_Q + delta tokens, "which reserves space for future token
+ * generation"; Sec. 3.1 "Adaptive Grouping", Eq. 4: when to regroup).
+ *
+ * Step s = 0, 1, ... of a decode loop:
+ *   1. pk_kv_append(step = s) writes the K/V rows of the token that every
+ *      request has just produced into the headroom behind its suffix in
+ *      kv_buf (buffer token suffix_off + L_Q + s; layout as documented at
+ *      pk_kv_buf_bytes).  k_new, v_new: device [n][Hkv][d], dtype, request
+ *      order.  Needs 0 <= s < headroom, else PK_EINVAL (no slot left: make a
+ *      new plan from the grown lengths and reorganize).
+ *   2. pk_packed_decode_attn_grown(grown = s + 1) is pk_packed_decode_attn
+ *      with every request's suffix extended by the `grown` appended tokens
+ *      (request i then has kv_len_i + grown keys).  grown in [0, headroom].
+ * Both use the plan's tables as they are; nothing is re-planned or copied.
+ * Calls of one step are ordered by the stream.
+ *
+ * pk_regroup_due evaluates the trigger of Eq. 4 after `steps` decode steps
+ * since the plan was made: with L_g(steps) = L(S_g) + steps * |S_g| (every
+ * member adds one unique token per step, prefixes do not grow) and
+ * DeltaL = max_g L_g - min_g L_g, it sets PK_REGROUP_DRIFT in *flags when
+ * steps * DeltaL >= C / 2, and PK_REGROUP_HEADROOM when steps >= headroom
+ * (the next append has no slot).  *drift (optional) receives DeltaL.  Host
+ * only, no device work.  Errors: PK_EINVAL (NULL, steps < 0).
+ */
+#define PK_REGROUP_DRIFT    1
+#define PK_REGROUP_HEADROOM 2
+int pk_kv_append(pk_plan* plan, const void* k_new, const void* v_new, void* kv_buf,
+                 int32_t step, int Hkv, int d, int dtype,
+                 void* workspace, size_t workspace_bytes, void* stream);
+int pk_packed_decode_attn_grown(pk_plan* plan, const void* q, const void* kv_buf,
+                                void* out, float scale, int32_t grown, int Hq, int Hkv, int d,
+                                int dtype, int out_dtype,
+                                void* workspace, size_t workspace_bytes, void* stream);
+int pk_regroup_due(const pk_plan* plan, int32_t steps, int32_t* flags, int64_t* drift);
 
 /* ------------------------------------------------------------------------
  * In-run comparison: per-request padded execution (Sec. 2.2: request-aligned

@@ -66,6 +66,12 @@ def lib():
     L.pk_packed_decode_attn.argtypes = [vp, vp, vp, vp, f32, ci, ci, ci, ci, ci, vp, sz, vp]
     L.pk_padded_decode_attn.restype = ci
     L.pk_padded_decode_attn.argtypes = [vp, vp, vp, vp, vp, i32, i32, i64, vp, f32, ci, ci, ci, ci, ci, vp, sz, vp]
+    L.pk_packed_decode_attn_grown.restype = ci
+    L.pk_packed_decode_attn_grown.argtypes = [vp, vp, vp, vp, f32, i32, ci, ci, ci, ci, ci, vp, sz, vp]
+    L.pk_kv_append.restype = ci
+    L.pk_kv_append.argtypes = [vp, vp, vp, vp, i32, ci, ci, ci, vp, sz, vp]
+    L.pk_regroup_due.restype = ci
+    L.pk_regroup_due.argtypes = [vp, i32, ctypes.POINTER(i32), ctypes.POINTER(i64)]
     L.pk_plan_stat.restype = i64
     L.pk_plan_stat.argtypes = [vp, ci]
     L.pk_last_error.restype = ctypes.c_char_p
@@ -80,7 +86,9 @@ EXPORTS = [
     "pk_plan_serialize", "pk_kv_buf_bytes", "pk_workspace_bytes", "pk_plan_bind",
     "pk_kv_reorganize", "pk_packed_prefill_attn", "pk_packed_decode_attn",
     "pk_padded_prefill_attn", "pk_padded_decode_attn", "pk_plan_stat", "pk_last_error",
+    "pk_kv_append", "pk_packed_decode_attn_grown", "pk_regroup_due",
 ]
+REGROUP_DRIFT, REGROUP_HEADROOM = 1, 2
 
 
 def _check(rc, what):
@@ -248,6 +256,33 @@ def packed_decode_attn(plan, q, kv_buf, out, scale, Hkv, workspace, stream=None)
         workspace.numel() * workspace.element_size(), _stream(stream))
     _check(rc, "pk_packed_decode_attn")
     return out
+
+
+def packed_decode_attn_grown(plan, q, kv_buf, out, scale, grown, Hkv, workspace, stream=None):
+    n, Hq, d = q.shape
+    rc = lib().pk_packed_decode_attn_grown(
+        plan.handle, _ptr(q), _ptr(kv_buf), _ptr(out), float(scale), int(grown), Hq, Hkv, d,
+        _dtype_code(q), _dtype_code(out), _ptr(workspace),
+        workspace.numel() * workspace.element_size(), _stream(stream))
+    _check(rc, "pk_packed_decode_attn_grown")
+    return out
+
+
+def kv_append(plan, k_new, v_new, kv_buf, step, workspace, stream=None):
+    n, Hkv, d = k_new.shape
+    rc = lib().pk_kv_append(
+        plan.handle, _ptr(k_new), _ptr(v_new), _ptr(kv_buf), int(step), Hkv, d, _dtype_code(k_new),
+        _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
+    _check(rc, "pk_kv_append")
+    return kv_buf
+
+
+def regroup_due(plan, steps):
+    """(flags, drift): flags is a bit set of REGROUP_DRIFT / REGROUP_HEADROOM."""
+    flags, drift = ctypes.c_int32(0), ctypes.c_int64(0)
+    rc = lib().pk_regroup_due(plan.handle, int(steps), ctypes.byref(flags), ctypes.byref(drift))
+    _check(rc, "pk_regroup_due")
+    return flags.value, drift.value
 
 
 def padded_decode_attn(plan, q, k_pages, v_pages, block_table, out, scale, workspace, stream=None):

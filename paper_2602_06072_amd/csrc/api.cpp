@@ -217,20 +217,25 @@ extern "C" int pk_padded_prefill_attn(pk_plan* plan, const void* q, const void* 
     return prefill_common(plan, q, k, v, out, scale, Hq, Hkv, d, dtype, out_dtype, workspace, workspace_bytes, stream, true);
 }
 
-extern "C" int pk_packed_decode_attn(pk_plan* plan, const void* q, const void* kv_buf,
-                                     void* out, float scale, int Hq, int Hkv, int d,
-                                     int dtype, int out_dtype,
-                                     void* workspace, size_t workspace_bytes, void* stream) {
+namespace {
+
+int decode_common(const char* who, pk_plan* plan, const void* q, const void* kv_buf,
+                  void* out, float scale, int32_t grown, int Hq, int Hkv, int d,
+                  int dtype, int out_dtype,
+                  void* workspace, size_t workspace_bytes, void* stream) {
+    const std::string w(who);
     std::string why;
-    if (!plan) return fail(PK_EINVAL, "pk_packed_decode_attn: plan is NULL");
+    if (!plan) return fail(PK_EINVAL, w + ": plan is NULL");
     if (plan->n == 0) return PK_OK;
-    if (!plan->decode_only) return fail(PK_EINVAL, "pk_packed_decode_attn: the plan must have q_len == 1 for every request");
-    if (!q || !kv_buf || !out) return fail(PK_EINVAL, "pk_packed_decode_attn: NULL pointer");
-    if (!shape_ok(Hq, Hkv, d, dtype, why)) return fail(PK_EINVAL, "pk_packed_decode_attn: " + why);
-    if (out_dtype != PK_BF16 && out_dtype != PK_F32) return fail(PK_EINVAL, "pk_packed_decode_attn: bad out_dtype");
-    if (dtype == PK_BF16 && (d != 64 && d != 128)) return fail(PK_EUNSUPPORTED, "pk_packed_decode_attn: bf16 path needs d in {64,128}");
-    if (dtype == PK_BF16 && Hq / Hkv > 32) return fail(PK_EUNSUPPORTED, "pk_packed_decode_attn: bf16 path needs Hq/Hkv <= 32");
-    if (dtype == PK_F32 && d > 256) return fail(PK_EUNSUPPORTED, "pk_packed_decode_attn: fp32 path needs d <= 256");
+    if (!plan->decode_only) return fail(PK_EINVAL, w + ": the plan must have q_len == 1 for every request");
+    if (!q || !kv_buf || !out) return fail(PK_EINVAL, w + ": NULL pointer");
+    if (grown < 0 || grown > plan->headroom)
+        return fail(PK_EINVAL, w + ": grown must be in [0, headroom] (regroup when the headroom is used up)");
+    if (!shape_ok(Hq, Hkv, d, dtype, why)) return fail(PK_EINVAL, w + ": " + why);
+    if (out_dtype != PK_BF16 && out_dtype != PK_F32) return fail(PK_EINVAL, w + ": bad out_dtype");
+    if (dtype == PK_BF16 && (d != 64 && d != 128)) return fail(PK_EUNSUPPORTED, w + ": bf16 path needs d in {64,128}");
+    if (dtype == PK_BF16 && Hq / Hkv > 32) return fail(PK_EUNSUPPORTED, w + ": bf16 path needs Hq/Hkv <= 32");
+    if (dtype == PK_F32 && d > 256) return fail(PK_EUNSUPPORTED, w + ": fp32 path needs d <= 256");
     int rc = ensure_bound(plan, Hq, Hkv, d, dtype, workspace, workspace_bytes, stream);
     if (rc != PK_OK) return rc;
     const DeviceTables& t = plan->tables;
@@ -244,8 +249,71 @@ extern "C" int pk_packed_decode_attn(pk_plan* plan, const void* q, const void* k
     a.part_lse = a.part_o + static_cast<size_t>(t.n_dec_parts) * Hq * d;
     a.buf_tokens = plan->buf_tokens; a.n = plan->n;
     a.Hq = Hq; a.Hkv = Hkv; a.d = d; a.scale = scale; a.out_f32 = out_dtype == PK_F32;
+    a.grown = grown;
     const int e = dtype == PK_BF16 ? launch_decode_bf16(a, stream) : launch_decode_f32(a, stream);
-    return e ? hip_fail("pk_packed_decode_attn", e) : PK_OK;
+    return e ? hip_fail(who, e) : PK_OK;
+}
+
+}  // namespace
+
+extern "C" int pk_packed_decode_attn(pk_plan* plan, const void* q, const void* kv_buf,
+                                     void* out, float scale, int Hq, int Hkv, int d,
+                                     int dtype, int out_dtype,
+                                     void* workspace, size_t workspace_bytes, void* stream) {
+    return decode_common("pk_packed_decode_attn", plan, q, kv_buf, out, scale, 0, Hq, Hkv, d, dtype, out_dtype,
+                         workspace, workspace_bytes, stream);
+}
+
+extern "C" int pk_packed_decode_attn_grown(pk_plan* plan, const void* q, const void* kv_buf,
+                                           void* out, float scale, int32_t grown, int Hq, int Hkv, int d,
+                                           int dtype, int out_dtype,
+                                           void* workspace, size_t workspace_bytes, void* stream) {
+    return decode_common("pk_packed_decode_attn_grown", plan, q, kv_buf, out, scale, grown, Hq, Hkv, d, dtype,
+                         out_dtype, workspace, workspace_bytes, stream);
+}
+
+extern "C" int pk_kv_append(pk_plan* plan, const void* k_new, const void* v_new, void* kv_buf,
+                            int32_t step, int Hkv, int d, int dtype,
+                            void* workspace, size_t workspace_bytes, void* stream) {
+    std::string why;
+    if (!plan) return fail(PK_EINVAL, "pk_kv_append: plan is NULL");
+    if (plan->n == 0) return PK_OK;
+    if (!plan->decode_only) return fail(PK_EINVAL, "pk_kv_append: the plan must have q_len == 1 for every request");
+    if (!k_new || !v_new || !kv_buf) return fail(PK_EINVAL, "pk_kv_append: NULL pointer");
+    if (step < 0 || step >= plan->headroom)
+        return fail(PK_EINVAL, "pk_kv_append: step must be in [0, headroom): no slot left, regroup");
+    int Hq = plan->tables.Hkv == Hkv && plan->tables.d == d && plan->tables.dtype == dtype ? plan->tables.Hq : Hkv;
+    if (!shape_ok(Hq, Hkv, d, dtype, why)) return fail(PK_EINVAL, "pk_kv_append: " + why);
+    if (dtype == PK_BF16 && d != 64 && d != 128) return fail(PK_EUNSUPPORTED, "pk_kv_append: bf16 path needs d in {64,128}");
+    int rc = ensure_bound(plan, Hq, Hkv, d, dtype, workspace, workspace_bytes, stream);
+    if (rc != PK_OK) return rc;
+    const DeviceTables& t = plan->tables;
+    AppendArgs a{};
+    a.k_new = k_new; a.v_new = v_new; a.kv_buf = kv_buf;
+    a.req_seg = tab(plan, t.dec_req_seg);
+    a.buf_tokens = plan->buf_tokens; a.n = plan->n; a.step = step; a.Hkv = Hkv; a.d = d;
+    const int e = dtype == PK_BF16 ? launch_append_bf16(a, stream) : launch_append_f32(a, stream);
+    return e ? hip_fail("pk_kv_append", e) : PK_OK;
+}
+
+extern "C" int pk_regroup_due(const pk_plan* plan, int32_t steps, int32_t* flags, int64_t* drift) {
+    if (!plan || !flags) return fail(PK_EINVAL, "pk_regroup_due: NULL pointer");
+    if (steps < 0) return fail(PK_EINVAL, "pk_regroup_due: steps must be non-negative");
+    int64_t lo = 0, hi = 0;
+    bool first = true;
+    for (const Group& g : plan->groups) {
+        const int64_t load = g.load + static_cast<int64_t>(steps) * static_cast<int64_t>(g.members.size());
+        if (first || load < lo) lo = load;
+        if (first || load > hi) hi = load;
+        first = false;
+    }
+    const int64_t dl = first ? 0 : hi - lo;
+    int32_t f = 0;
+    if (2 * static_cast<int64_t>(steps) * dl >= plan->token_budget) f |= PK_REGROUP_DRIFT;
+    if (steps >= plan->headroom) f |= PK_REGROUP_HEADROOM;
+    *flags = f;
+    if (drift) *drift = dl;
+    return PK_OK;
 }
 
 extern "C" int pk_padded_decode_attn(pk_plan* plan, const void* q,

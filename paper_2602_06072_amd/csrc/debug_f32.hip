@@ -115,7 +115,7 @@ __global__ __launch_bounds__(64) void decode_f32_kernel(DecodeArgs a) {
     const int32_t* seg = a.req_seg + 4 * i;                 // prefix_off, L_P, suffix_off, L_Q (absolute)
     for (int s = 0; s < 2; ++s) {
         const int64_t off = (static_cast<int64_t>(g) * a.buf_tokens + seg[2 * s]) * a.d;
-        attend_segment(st, q_s, s_s, kb + off, vb + off, seg[2 * s + 1], a.d, a.d, a.scale);
+        attend_segment(st, q_s, s_s, kb + off, vb + off, seg[2 * s + 1] + (s == 1 ? a.grown : 0), a.d, a.d, a.scale);
     }
     store_row(st, a.out, (static_cast<int64_t>(i) * a.Hq + h) * a.d, a.d, a.out_f32);
 }
@@ -144,7 +144,29 @@ __global__ __launch_bounds__(256) void reorg_f32_kernel(ReorgArgs a) {
     }
 }
 
+// the token of decode step `step` into its request's headroom (fp32 layout)
+__global__ __launch_bounds__(256) void append_f32_kernel(AppendArgs a) {
+    const int i = blockIdx.x, h = blockIdx.y;
+    const int32_t* seg = a.req_seg + 4 * i;
+    const int64_t tok = static_cast<int64_t>(seg[2]) + seg[3] + a.step;
+    float* kb = static_cast<float*>(a.kv_buf);
+    float* vb = kb + static_cast<int64_t>(a.Hkv) * a.buf_tokens * a.d;
+    const int64_t src = (static_cast<int64_t>(i) * a.Hkv + h) * a.d;
+    const int64_t dst = (static_cast<int64_t>(h) * a.buf_tokens + tok) * a.d;
+    for (int c = threadIdx.x; c < a.d; c += blockDim.x) {
+        kb[dst + c] = static_cast<const float*>(a.k_new)[src + c];
+        vb[dst + c] = static_cast<const float*>(a.v_new)[src + c];
+    }
+}
+
 }  // namespace
+
+int launch_append_f32(const AppendArgs& a, void* stream) {
+    if (a.n == 0) return 0;
+    hipLaunchKernelGGL(append_f32_kernel, dim3(static_cast<unsigned>(a.n), static_cast<unsigned>(a.Hkv)), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), a);
+    return static_cast<int>(hipGetLastError());
+}
 
 int launch_prefill_f32(const PrefillArgs& a, void* stream) {
     if (a.total_q_rows == 0) return 0;

@@ -25,7 +25,8 @@ __device__ __forceinline__ void decode_body(const DecodeArgs& a, const int item,
     const int lane = threadIdx.x, n = lane & 15, g = lane >> 4;
     const int r = a.Hq / a.Hkv;
     const int32_t* it = a.items + 8 * static_cast<int64_t>(item);
-    const int tok_begin = it[0], tok_end = it[1], mem_first = it[2], n_mem = it[3];
+    // the last item of a suffix also covers the tokens appended since the plan was made
+    const int tok_begin = it[0], tok_end = it[1] + (it[4] ? a.grown : 0), mem_first = it[2], n_mem = it[3];
     const int64_t n_tiles = a.buf_tokens / 32;
     const u32x4* base = static_cast<const u32x4*>(a.kv_buf) + static_cast<int64_t>(kvh) * n_tiles * TILE_U4 + lane;
     const int b0 = tok_begin / 32, b1 = (tok_end + 31) / 32;

@@ -16,6 +16,14 @@ struct ReorgArgs {
 int launch_reorg_bf16(const ReorgArgs& a, void* stream);
 int launch_reorg_f32(const ReorgArgs& a, void* stream);
 
+struct AppendArgs {
+    const void* k_new; const void* v_new;           // [n][Hkv][d]
+    void* kv_buf; const int32_t* req_seg;           // [n][4]: prefix_off, L_P, suffix_off, L_Q (absolute tokens)
+    int64_t buf_tokens; int32_t n; int32_t step; int Hkv; int d;
+};
+int launch_append_bf16(const AppendArgs& a, void* stream);
+int launch_append_f32(const AppendArgs& a, void* stream);
+
 struct DecodeArgs {
     const void* q; const void* kv_buf; void* out;
     const int32_t* items; int32_t n_items; int32_t n_wide;   // the first n_wide items have > 16 query rows
@@ -24,6 +32,7 @@ struct DecodeArgs {
     const int32_t* req_seg;
     float* part_o; float* part_lse;
     int64_t buf_tokens; int32_t n; int Hq; int Hkv; int d; float scale; int out_f32;
+    int32_t grown;                                  // tokens appended to every suffix since the plan was made
 };
 int launch_decode_bf16(const DecodeArgs& a, void* stream);
 int launch_decode_f32(const DecodeArgs& a, void* stream);

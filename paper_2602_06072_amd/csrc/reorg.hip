@@ -39,10 +39,8 @@ __global__ __launch_bounds__(256) void reorg_bf16_kernel(ReorgArgs a) {
         src_s[tid] = src;
     }
     __syncthreads();
-    bool any = false;
-    for (int t = 0; t < 32; ++t) any |= src_s[t] >= 0;
-    if (!any) return;                             // tile without valid tokens: not written
-
+    // (a tile without any valid token is written as zeros too: tokens appended later into the
+    // headroom share tiles with such slots, and a masked key must not meet stale bits in V)
     const u32x4* kp = static_cast<const u32x4*>(a.k_pages);
     const u32x4* vp = static_cast<const u32x4*>(a.v_pages);
     for (int x = tid; x < 32 * CH; x += 256) {
@@ -89,7 +87,44 @@ __global__ __launch_bounds__(256) void reorg_bf16_kernel(ReorgArgs a) {
     }
 }
 
+// The token that decode step `step` produced goes into the headroom behind its request's suffix
+// (Sec. 3.2, M(Q_i) = L_Q + delta), in the tile layout above.  One workgroup per (request, KV
+// head), one thread per column; a K row is D/8 whole 16-byte chunks, a V row is D single elements.
+template <int D>
+__global__ __launch_bounds__(D) void append_bf16_kernel(AppendArgs a) {
+    constexpr int CH = D / 8;
+    const int i = blockIdx.x, h = blockIdx.y, c = threadIdx.x;
+    const int32_t* seg = a.req_seg + 4 * i;
+    const int64_t tok = static_cast<int64_t>(seg[2]) + seg[3] + a.step;
+    const int64_t tile = tok / 32;
+    const int tt = static_cast<int>(tok % 32);
+    const int64_t n_tiles = a.buf_tokens / 32;
+    uint16_t* base = static_cast<uint16_t*>(a.kv_buf) + (static_cast<int64_t>(h) * n_tiles + tile) * (2 * 32 * CH) * 8;
+    const int64_t src = (static_cast<int64_t>(i) * a.Hkv + h) * D + c;
+    // K: chunk (u, s, l)[j] = K[16u + l%16][32s + 8(l/16) + j]
+    {
+        const int u = tt >> 4, s = c >> 5, gq = (c & 31) >> 3, j = c & 7, l = 16 * gq + (tt & 15);
+        base[((u * (D / 32) + s) * 64 + l) * 8 + j] = static_cast<const uint16_t*>(a.k_new)[src];
+    }
+    // V: chunk (t, l)[j] = V[kappa(l/16, j)][16t + l%16], kappa(g, j) = 4g + j (j < 4), 16 + 4g + (j - 4)
+    {
+        const int g = tt < 16 ? tt >> 2 : (tt - 16) >> 2, j = tt < 16 ? tt & 3 : 4 + ((tt - 16) & 3);
+        const int t = c >> 4, l = 16 * g + (c & 15);
+        base[(32 * CH + t * 64 + l) * 8 + j] = static_cast<const uint16_t*>(a.v_new)[src];
+    }
+}
+
 }  // namespace
+
+int launch_append_bf16(const AppendArgs& a, void* stream) {
+    if (a.n == 0) return 0;
+    dim3 grid(static_cast<unsigned>(a.n), static_cast<unsigned>(a.Hkv));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (a.d == 128) hipLaunchKernelGGL(append_bf16_kernel<128>, grid, dim3(128), 0, st, a);
+    else if (a.d == 64) hipLaunchKernelGGL(append_bf16_kernel<64>, grid, dim3(64), 0, st, a);
+    else return static_cast<int>(hipErrorInvalidValue);
+    return static_cast<int>(hipGetLastError());
+}
 
 int launch_reorg_bf16(const ReorgArgs& a, void* stream) {
     const int64_t n_tiles = a.buf_tokens / 32;

@@ -82,16 +82,24 @@ void build_decode(const pk_plan& plan, int Hq, int Hkv, Builder& b, DeviceTables
     split = (split + kDecodeBlock - 1) / kDecodeBlock * kDecodeBlock;
     t.dec_split_tokens = static_cast<int32_t>(split);
 
-    struct Item { int64_t a, e; std::vector<int32_t> reqs; };
+    struct Item { int64_t a, e; std::vector<int32_t> reqs; bool grows = false; };
     std::vector<Item> items;
-    auto add_segment = [&](int64_t a, int64_t e, const std::vector<int32_t>& reqs) {
-        if (e <= a) return;
+    // suffix: the segment is a request's private suffix; its last item is marked so that the
+    // kernel extends it by the tokens appended into the headroom since the plan was made (an
+    // empty suffix with headroom still gets an item for them)
+    auto add_segment = [&](int64_t a, int64_t e, const std::vector<int32_t>& reqs, bool suffix) {
+        if (e <= a) {
+            if (suffix && plan.headroom > 0) { items.push_back({a, a, reqs}); items.back().grows = true; }
+            return;
+        }
         const int64_t a_blk = a / kDecodeBlock * kDecodeBlock;
         for (size_t m0 = 0; m0 < reqs.size(); m0 += max_members) {
             std::vector<int32_t> chunk(reqs.begin() + m0,
                                        reqs.begin() + std::min(reqs.size(), m0 + max_members));
-            for (int64_t p0 = a_blk; p0 < e; p0 += split)
+            for (int64_t p0 = a_blk; p0 < e; p0 += split) {
                 items.push_back({std::max(a, p0), std::min(e, p0 + split), chunk});
+                items.back().grows = suffix && p0 + split >= e;
+            }
         }
     };
     std::vector<int32_t> req_seg(static_cast<size_t>(plan.n) * 4, 0);
@@ -105,11 +113,11 @@ void build_decode(const pk_plan& plan, int Hq, int Hkv, Builder& b, DeviceTables
                        g.members[j].prefix_off == m.prefix_off) ++j;
                 std::vector<int32_t> fam;
                 for (size_t k = i; k < j; ++k) fam.push_back(g.members[k].req);
-                add_segment(g.buf_base + m.prefix_off, g.buf_base + m.prefix_off + m.lp, fam);
+                add_segment(g.buf_base + m.prefix_off, g.buf_base + m.prefix_off + m.lp, fam, false);
             }
             for (size_t k = i; k < j; ++k) {
                 const Member& mm = g.members[k];
-                add_segment(g.buf_base + mm.suffix_off, g.buf_base + mm.suffix_off + mm.lq, {mm.req});
+                add_segment(g.buf_base + mm.suffix_off, g.buf_base + mm.suffix_off + mm.lq, {mm.req}, true);
                 int32_t* rs = &req_seg[static_cast<size_t>(mm.req) * 4];
                 rs[0] = static_cast<int32_t>(g.buf_base + mm.prefix_off); rs[1] = mm.lp;
                 rs[2] = static_cast<int32_t>(g.buf_base + mm.suffix_off); rs[3] = mm.lq;
@@ -148,7 +156,7 @@ void build_decode(const pk_plan& plan, int Hq, int Hkv, Builder& b, DeviceTables
         flat.push_back(static_cast<int32_t>(it.e));
         flat.push_back(static_cast<int32_t>(members.size()));
         flat.push_back(static_cast<int32_t>(it.reqs.size()));
-        flat.push_back(0); flat.push_back(0); flat.push_back(0); flat.push_back(0);
+        flat.push_back(it.grows ? 1 : 0); flat.push_back(0); flat.push_back(0); flat.push_back(0);
         for (int32_t rq : it.reqs) {
             members.push_back(rq);
             member_slot.push_back(n_items_of[static_cast<size_t>(rq)] > 1 ? next_slot[static_cast<size_t>(rq)]++ : -1);

@@ -140,3 +140,48 @@ def test_sizes_and_stats():
     assert plan.stat(2) >= plan.stat(1)                       # padding never issues less than packing
     assert plan.buf_tokens % pk.PK_KV_BLOCK == 0
     assert plan.kv_buf_bytes(8, 128, pk.PK_BF16) == plan.buf_tokens * 8 * 128 * 2 * 2
+
+
+# ---- decode-step evolution: the Eq. 4 trigger and the headroom bookkeeping are host logic -----
+@settings(max_examples=300, deadline=None)
+@given(plan_inputs(), st.integers(0, 400))
+def test_regroup_trigger_equals_oracle(inp, t):
+    kv, pid, plen, C, hr = inp
+    ones = [1] * len(kv)
+    plan = pk.pack_plan(kv, ones, pid, plen, C, hr)
+    oplan = opl.make_plan(kv, ones, pid, plen, C, hr)
+    flags, drift = pk.regroup_due(plan, t)
+    assert drift == opl.drift_after(oplan, t)
+    assert bool(flags & pk.REGROUP_DRIFT) == opl.regroup_due(oplan, t)
+    assert bool(flags & pk.REGROUP_HEADROOM) == opl.headroom_exhausted(oplan, t)
+
+
+def test_regroup_trigger_on_a_skewed_decode_batch():
+    # two groups of very different member counts drift apart by (m1 - m0) tokens per step
+    kv = [500] + [10] * 49
+    plan = pk.pack_plan(kv, [1] * 50, token_budget=512, headroom=64)
+    assert plan.num_groups == 2
+    fired = [t for t in range(0, 65) if pk.regroup_due(plan, t)[0] & pk.REGROUP_DRIFT]
+    # loads 500 (1 member) and 490 (49 members): DeltaL(t) = |10 - 48 t|, t * DeltaL >= 256 from t = 3 on
+    assert fired and fired[0] == 3 and fired == list(range(3, 65))
+    assert pk.regroup_due(plan, 64)[0] & pk.REGROUP_HEADROOM
+    assert not pk.regroup_due(plan, 63)[0] & pk.REGROUP_HEADROOM
+
+
+def test_step_entry_points_validate_before_touching_the_device():
+    L = pk.lib()
+    dummy = ctypes.create_string_buffer(16)
+    p = ctypes.addressof(dummy)
+    plan = pk.pack_plan([4, 4], [1, 1], token_budget=8, headroom=2)
+    flags = ctypes.c_int32(0)
+    assert L.pk_regroup_due(None, 0, ctypes.byref(flags), None) == -1
+    assert L.pk_regroup_due(plan.handle, -1, ctypes.byref(flags), None) == -1
+    assert L.pk_regroup_due(plan.handle, 0, None, None) == -1
+    assert L.pk_kv_append(None, p, p, p, 0, 2, 64, 0, p, 16, None) == -1
+    assert L.pk_kv_append(plan.handle, None, p, p, 0, 2, 64, 0, p, 16, None) == -1
+    assert L.pk_kv_append(plan.handle, p, p, p, 2, 2, 64, 0, p, 16, None) == -1       # no slot left
+    assert L.pk_kv_append(plan.handle, p, p, p, -1, 2, 64, 0, p, 16, None) == -1
+    assert b"regroup" in L.pk_last_error()
+    assert L.pk_packed_decode_attn_grown(plan.handle, p, p, p, 1.0, 3, 4, 2, 64, 0, 0, p, 16, None) == -1   # grown > headroom
+    prefill_plan = pk.pack_plan([4, 4], token_budget=8, headroom=2)
+    assert L.pk_kv_append(prefill_plan.handle, p, p, p, 0, 2, 64, 0, p, 16, None) == -1   # not a decode plan
