@@ -178,6 +178,56 @@ def bench_decode(w, iters, with_padded=True):
     return res
 
 
+def bench_multistep(w, steps=32):
+    """Decoding `steps` tokens with ONE plan made with headroom = steps (Sec. 3.2): the re-layout
+    runs once, every step appends the new K/V rows into the headroom and decodes over the grown
+    buffer.  Reports the amortised cost per step next to re-organising before every step, and
+    the step at which the regrouping rule of Eq. 4 first fires for this batch."""
+    import torch
+    from paper_2602_06072_amd import binding as pk
+    dev = w.q.device
+    ones = np.ones_like(w.kv_lens)
+    plan = pk.pack_plan(w.kv_lens, ones, w.prefix_ids, w.prefix_lens, w.token_budget, steps)
+    ws = pk.new_workspace(plan, w.Hq, w.Hkv, w.d, pk.PK_BF16)
+    pk.plan_bind(plan, w.Hq, w.Hkv, w.d, pk.PK_BF16, ws)
+    kv_buf = pk.new_kv_buf(plan, w.Hkv, w.d, pk.PK_BF16)
+    bt = torch.from_numpy(w.block_table).to(dev)
+    out = torch.empty(w.q.shape, dtype=torch.bfloat16, device=dev)
+    g = torch.Generator(device="cpu").manual_seed(11)
+    k_new = torch.randn((w.n, w.Hkv, w.d), generator=g).to(torch.bfloat16).to(dev)
+    v_new = torch.randn((w.n, w.Hkv, w.d), generator=g).to(torch.bfloat16).to(dev)
+
+    def run():
+        pk.kv_reorganize(plan, w.k_pages, w.v_pages, bt, kv_buf, ws)
+        for s in range(steps):
+            pk.kv_append(plan, k_new, v_new, kv_buf, s, ws)
+            pk.packed_decode_attn_grown(plan, w.q, kv_buf, out, w.scale, s + 1, w.Hkv, ws)
+
+    run()
+    torch.cuda.synchronize()
+    reorg_ms, _ = _time_launches(lambda: pk.kv_reorganize(plan, w.k_pages, w.v_pages, bt, kv_buf, ws), 10)
+    append_ms, _ = _time_launches(lambda: pk.kv_append(plan, k_new, v_new, kv_buf, 0, ws), 20)
+    dec_ms, _ = _time_launches(lambda: pk.packed_decode_attn_grown(plan, w.q, kv_buf, out, w.scale, steps, w.Hkv, ws), 20)
+    total_ms, _ = _time_launches(run, 5, warmup=1)
+    fire = fire_in = 0
+    for t in range(1, 100001):
+        f = pk.regroup_due(plan, t)[0]
+        if not fire and f & pk.REGROUP_DRIFT:
+            fire = t
+        if not fire_in and f & pk.REGROUP_DRIFT_WITHIN_BUDGET:
+            fire_in = t
+        if fire and fire_in:
+            break
+    return {"steps": steps, "headroom": steps, "groups": plan.num_groups,
+            "reorg_once_ms": reorg_ms, "append_ms": append_ms, "decode_grown_ms": dec_ms,
+            "sequence_ms": total_ms, "per_step_ms": total_ms / steps,
+            "per_step_ms_if_reorganised_every_step": reorg_ms + dec_ms,
+            "amortised_reorg_ms_per_step": reorg_ms / steps,
+            "regroup_rule_first_fires_at_step": fire,
+            "regroup_rule_without_oversize_groups_first_fires_at_step": fire_in,
+            "token_budget": int(w.token_budget)}
+
+
 def cpu_baseline(w):
     """The oracle as it stands, timed on every second query row of the batch."""
     from oracle import attention as oa
@@ -246,6 +296,7 @@ def main():
     if not args.no_extras:
         w3 = wl.config3(args.seed, device=dev)
         extra["decode_cfg3"] = bench_decode(w3, 20)
+        extra["decode_cfg3_32_steps"] = bench_multistep(w3, 32)
         del w3
         w4 = wl.config4(args.seed, device=dev)
         extra["decode_cfg4_shared_prefix"] = bench_decode(w4, 20)

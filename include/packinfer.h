@@ -215,11 +215,16 @@ int pk_packed_decode_attn(pk_plan* plan, const void* q, const void* kv_buf,
  * member adds one unique token per step, prefixes do not grow) and
  * DeltaL = max_g L_g - min_g L_g, it sets PK_REGROUP_DRIFT in *flags when
  * steps * DeltaL >= C / 2, and PK_REGROUP_HEADROOM when steps >= headroom
- * (the next append has no slot).  *drift (optional) receives DeltaL.  Host
- * only, no device work.  Errors: PK_EINVAL (NULL, steps < 0).
+ * (the next append has no slot).  *drift (optional) receives DeltaL.
+ * PK_REGROUP_DRIFT_WITHIN_BUDGET is the same rule over the groups whose
+ * initial load is at most C: a group that Alg. 1 opened for one item longer
+ * than C cannot be balanced by regrouping and makes the plain rule fire at
+ * the first step.  Host only, no device work.
+ * Errors: PK_EINVAL (NULL, steps < 0).
  */
-#define PK_REGROUP_DRIFT    1
-#define PK_REGROUP_HEADROOM 2
+#define PK_REGROUP_DRIFT               1
+#define PK_REGROUP_HEADROOM            2
+#define PK_REGROUP_DRIFT_WITHIN_BUDGET 4
 int pk_kv_append(pk_plan* plan, const void* k_new, const void* v_new, void* kv_buf,
                  int32_t step, int Hkv, int d, int dtype,
                  void* workspace, size_t workspace_bytes, void* stream);

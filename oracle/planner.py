@@ -155,21 +155,26 @@ def make_plan(kv_lens: Sequence[int], q_lens: Optional[Sequence[int]] = None,
 
 
 # ---- decode-step evolution (Sec. 3.1 "Adaptive Grouping", Eq. 4; Sec. 3.2 headroom) ----------
-def group_loads_after(plan: Plan, t: int) -> List[int]:
+def group_loads_after(plan: Plan, t: int, within_budget_only: bool = False) -> List[int]:
     """L(S_g) after t decode steps: every member of a group has produced t new tokens, each of
-    which is a unique suffix token of that group (prefixes do not grow)."""
-    return [g.load + t * len(g.members) for g in plan.groups]
+    which is a unique suffix token of that group (prefixes do not grow).
+
+    within_budget_only leaves out the groups that the else-branch of Alg. 1 opened for an item
+    longer than C: no regrouping can balance those, and the rule below would fire for them at
+    the first step (a reading of this build, not of the paper)."""
+    return [g.load + t * len(g.members) for g in plan.groups
+            if not (within_budget_only and g.load > plan.token_budget)]
 
 
-def drift_after(plan: Plan, t: int) -> int:
+def drift_after(plan: Plan, t: int, within_budget_only: bool = False) -> int:
     """Delta L = |max_g L(S_g) - min_g L(S_g)| with the loads as they stand after t steps."""
-    loads = group_loads_after(plan, t)
+    loads = group_loads_after(plan, t, within_budget_only)
     return max(loads) - min(loads) if loads else 0
 
 
-def regroup_due(plan: Plan, t: int) -> bool:
+def regroup_due(plan: Plan, t: int, within_budget_only: bool = False) -> bool:
     """Eq. 4: regroup once t * Delta L >= C / 2, t counted from the last (re)grouping."""
-    return 2 * t * drift_after(plan, t) >= plan.token_budget
+    return 2 * t * drift_after(plan, t, within_budget_only) >= plan.token_budget
 
 
 def headroom_exhausted(plan: Plan, t: int) -> bool:

@@ -88,7 +88,7 @@ EXPORTS = [
     "pk_padded_prefill_attn", "pk_padded_decode_attn", "pk_plan_stat", "pk_last_error",
     "pk_kv_append", "pk_packed_decode_attn_grown", "pk_regroup_due",
 ]
-REGROUP_DRIFT, REGROUP_HEADROOM = 1, 2
+REGROUP_DRIFT, REGROUP_HEADROOM, REGROUP_DRIFT_WITHIN_BUDGET = 1, 2, 4
 
 
 def _check(rc, what):
@@ -278,7 +278,7 @@ def kv_append(plan, k_new, v_new, kv_buf, step, workspace, stream=None):
 
 
 def regroup_due(plan, steps):
-    """(flags, drift): flags is a bit set of REGROUP_DRIFT / REGROUP_HEADROOM."""
+    """(flags, drift): flags is a bit set of REGROUP_DRIFT / REGROUP_HEADROOM / REGROUP_DRIFT_WITHIN_BUDGET."""
     flags, drift = ctypes.c_int32(0), ctypes.c_int64(0)
     rc = lib().pk_regroup_due(plan.handle, int(steps), ctypes.byref(flags), ctypes.byref(drift))
     _check(rc, "pk_regroup_due")

@@ -299,18 +299,23 @@ extern "C" int pk_kv_append(pk_plan* plan, const void* k_new, const void* v_new,
 extern "C" int pk_regroup_due(const pk_plan* plan, int32_t steps, int32_t* flags, int64_t* drift) {
     if (!plan || !flags) return fail(PK_EINVAL, "pk_regroup_due: NULL pointer");
     if (steps < 0) return fail(PK_EINVAL, "pk_regroup_due: steps must be non-negative");
-    int64_t lo = 0, hi = 0;
-    bool first = true;
+    // [0]: all groups; [1]: without the groups opened for an item longer than C
+    int64_t lo[2] = {0, 0}, hi[2] = {0, 0};
+    bool first[2] = {true, true};
     for (const Group& g : plan->groups) {
         const int64_t load = g.load + static_cast<int64_t>(steps) * static_cast<int64_t>(g.members.size());
-        if (first || load < lo) lo = load;
-        if (first || load > hi) hi = load;
-        first = false;
+        for (int k = 0; k < 2; ++k) {
+            if (k == 1 && g.load > plan->token_budget) continue;
+            if (first[k] || load < lo[k]) lo[k] = load;
+            if (first[k] || load > hi[k]) hi[k] = load;
+            first[k] = false;
+        }
     }
-    const int64_t dl = first ? 0 : hi - lo;
+    const int64_t dl = first[0] ? 0 : hi[0] - lo[0], dl_in = first[1] ? 0 : hi[1] - lo[1];
     int32_t f = 0;
     if (2 * static_cast<int64_t>(steps) * dl >= plan->token_budget) f |= PK_REGROUP_DRIFT;
     if (steps >= plan->headroom) f |= PK_REGROUP_HEADROOM;
+    if (2 * static_cast<int64_t>(steps) * dl_in >= plan->token_budget) f |= PK_REGROUP_DRIFT_WITHIN_BUDGET;
     *flags = f;
     if (drift) *drift = dl;
     return PK_OK;

@@ -154,6 +154,7 @@ def test_regroup_trigger_equals_oracle(inp, t):
     assert drift == opl.drift_after(oplan, t)
     assert bool(flags & pk.REGROUP_DRIFT) == opl.regroup_due(oplan, t)
     assert bool(flags & pk.REGROUP_HEADROOM) == opl.headroom_exhausted(oplan, t)
+    assert bool(flags & pk.REGROUP_DRIFT_WITHIN_BUDGET) == opl.regroup_due(oplan, t, within_budget_only=True)
 
 
 def test_regroup_trigger_on_a_skewed_decode_batch():

@@ -100,3 +100,19 @@ def test_headroom_slots():
     # all headroom rows are used exactly once, nothing else was touched
     assert len(taken) == total
     assert np.count_nonzero(buf[:, 0, 0] != -1.0) == plan.headroom * 3
+
+
+def test_groups_longer_than_the_budget_can_be_left_out():
+    # Alg. 1 by hand: L_total = 1297, C = 256 -> 6 initial groups; 900 fits none and opens a seventh
+    # (else-branch); 100, 100, 99, 98 go to the four emptiest groups one each; the two groups that
+    # stay empty are dropped.  Loads in group order: 100, 100, 99, 98, 900, one member each.
+    plan = planner.make_plan([900, 100, 100, 99, 98], None, None, None, token_budget=256, headroom=4)
+    loads = [g.load for g in plan.groups]
+    assert loads == [100, 100, 99, 98, 900] and all(len(g.members) == 1 for g in plan.groups)
+    assert planner.regroup_due(plan, 1)                              # |900 - 98| >= 128 at once
+    assert not planner.regroup_due(plan, 1, within_budget_only=True)
+    # without the oversize group DeltaL stays 2 (equal member counts): t * 2 >= 128 first at t = 64
+    first = next(t for t in range(1, 1000) if planner.regroup_due(plan, t, within_budget_only=True))
+    assert first == 64
+    assert planner.group_loads_after(plan, 3, within_budget_only=True) == [103, 103, 102, 101]
+    assert planner.drift_after(plan, 3) == 900 - 98 and planner.drift_after(plan, 3, within_budget_only=True) == 2
