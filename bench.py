@@ -228,6 +228,41 @@ def bench_multistep(w, steps=32):
             "token_budget": int(w.token_budget)}
 
 
+def capacity_sweep(wl, pk, seed, dev):
+    """Offline profiling of the group capacity C (Sec. 3.1 "Adaptive Grouping": C is found by
+    profiling a range of group lengths): packed prefill kernel time and issued/useful work on
+    configuration 2, re-layout + decode time on configuration 3, for a range of C."""
+    import torch
+    rows = []
+    w2 = wl.config2(seed, device=dev)
+    out2 = torch.empty(w2.q.shape, dtype=torch.bfloat16, device=dev)
+    w3 = wl.config3(seed, device=dev)
+    out3 = torch.empty(w3.q.shape, dtype=torch.bfloat16, device=dev)
+    bt = torch.from_numpy(w3.block_table).to(dev)
+    ones = np.ones_like(w3.kv_lens)
+    for C in (512, 1024, 2048, 4096, 8192, 16384, 32768, 65536):
+        plan = pk.pack_plan(w2.kv_lens, w2.q_lens, token_budget=C)
+        ws = pk.new_workspace(plan, w2.Hq, w2.Hkv, w2.d, pk.PK_BF16)
+        pk.plan_bind(plan, w2.Hq, w2.Hkv, w2.d, pk.PK_BF16, ws)
+        ms, _ = _time_launches(lambda: pk.packed_prefill_attn(plan, w2.q, w2.k, w2.v, out2, w2.scale, ws), 20)
+        row = {"C": C, "prefill_groups": plan.num_groups, "prefill_q_tiles": plan.stat(6),
+               "prefill_useful_over_issued": plan.stat(0) / max(1, plan.stat(1)), "prefill_kernel_ms": ms,
+               "prefill_tflops": prefill_flops(w2, plan.stat(0)) / (ms * 1e-3) / 1e12}
+        plan3 = pk.pack_plan(w3.kv_lens, ones, w3.prefix_ids, w3.prefix_lens, C)
+        ws3 = pk.new_workspace(plan3, w3.Hq, w3.Hkv, w3.d, pk.PK_BF16)
+        pk.plan_bind(plan3, w3.Hq, w3.Hkv, w3.d, pk.PK_BF16, ws3)
+        buf = pk.new_kv_buf(plan3, w3.Hkv, w3.d, pk.PK_BF16)
+        r_ms, _ = _time_launches(lambda: pk.kv_reorganize(plan3, w3.k_pages, w3.v_pages, bt, buf, ws3), 10)
+        d_ms, _ = _time_launches(lambda: pk.packed_decode_attn(plan3, w3.q, buf, out3, w3.scale, w3.Hkv, ws3), 20)
+        loads = [g["load"] for g in plan3.groups()]
+        row.update({"decode_groups": plan3.num_groups, "decode_buf_tokens": plan3.buf_tokens,
+                    "decode_max_over_mean_load": max(loads) / (sum(loads) / len(loads)),
+                    "reorg_ms": r_ms, "decode_ms": d_ms})
+        rows.append(row)
+        del buf, ws3, ws
+    return rows
+
+
 def cpu_baseline(w):
     """The oracle as it stands, timed on every second query row of the batch."""
     from oracle import attention as oa
@@ -266,6 +301,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain elementwise kernel over 1 GiB 5 times (reference for HBM byte counters)")
+    ap.add_argument("--capacity-sweep", action="store_true",
+                    help="instead of the benchmark line: profile the group capacity C over a range (one JSON line)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this hot path runs on ONE GPU (no sharding, no collectives); use --gpus 1",
@@ -281,6 +318,11 @@ def main():
     pk.lib()                                          # fail loudly if the HIP library is missing
     dev = "cuda:0"
     torch.cuda.set_device(0)
+
+    if args.capacity_sweep:
+        print(json.dumps({"capacity_sweep": capacity_sweep(wl, pk, args.seed, dev), "seed": args.seed,
+                          "workloads": "configs[1] prefill, configs[2] decode"}))
+        return
 
     if args.calibrate_copy:
         # an elementwise kernel that reads 1 GiB and writes 1 GiB (bf16 x 2 -> bf16)

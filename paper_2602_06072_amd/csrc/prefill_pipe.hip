@@ -47,7 +47,7 @@ __device__ __forceinline__ bf16x8 v_operand(const unsigned char* vs, const LaneO
 
 // What a workgroup works on, and this lane's share of it.
 struct WorkUnit {
-    int head, kvh, n_kv, n_active, wave, lane, n, hlf;   // n_active: key tiles before this wave's trailing skips
+    int head, kvh, n_kv, n_lead, n_active, wave, lane, n, hlf;   // this wave computes key tiles [n_lead, n_active)
     int qrow, lo, hi;                  // this lane's query row (-1: padding) and its key range [lo, hi)
     const int32_t* kvt;                // key-tile list of the query tile: (first key row, info) pairs
     int64_t row_bytes;                 // bytes between consecutive K/V rows in global memory
@@ -75,6 +75,7 @@ __device__ __forceinline__ bool setup(const PrefillArgs& a, WorkUnit& u, LaneOff
     u.lane = tid & 63; u.n = u.lane & 31; u.hlf = u.lane >> 5;
     u.wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     u.n_active = u.n_kv - ((desc[3] >> (8 * u.wave)) & 0xFF);
+    u.n_lead = min((desc[2] >> (8 * u.wave)) & 0xFF, u.n_active);
     const int rr = tile * BM + u.wave * 32 + u.n;
     u.qrow = a.row_q[rr]; u.lo = a.row_lo[rr]; u.hi = a.row_hi[rr];
     u.row_bytes = static_cast<int64_t>(a.Hkv) * ROWB;
@@ -399,6 +400,16 @@ __global__ __launch_bounds__(256, 2) void prefill_bf16_dma_kernel(PrefillArgs a)
     { const int vc = v_cur; v_cur = v_fill; v_fill = vc; }
 
     int j = 0;
+    // leading tiles that this wave skips: it only takes part in the barriers and in the copies,
+    // then picks up its first operands from the stage that is current by then
+    for (; j < u.n_lead; ++j) {
+        PK_BARRIER_AND_REFILL();
+        PK_ROTATE();
+    }
+    if (u.n_lead > 0) {
+#pragma unroll
+        for (int x = 0; x < 4; ++x) ring[x] = k_operand(lds + k_cur, off, 0, x);
+    }
     for (; j < u.n_active; ++j) {
         // a tile that this wave could skip inside its active range is computed as a masked one
         const bool masked = PK_CODE(e0i) != 2;

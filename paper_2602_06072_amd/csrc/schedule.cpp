@@ -262,18 +262,21 @@ void emit_sched(const SchedBuild& sb, const std::vector<int32_t>& order, Builder
     for (int32_t idx : order) {
         desc.push_back(static_cast<int32_t>(kv.size() / 2));
         desc.push_back(sb.n_kv[idx]);
-        desc.push_back(sb.n_rows[idx]);
-        // per wave (8 bits each, saturating): how many key tiles at the END of the list the wave skips
-        int32_t trailing = 0;
+        // per wave (8 bits each, saturating): how many key tiles at the START and at the END of the
+        // list the wave skips (a packed query tile that straddles requests lists the key tiles of all
+        // of them; the rows of one wave mostly belong to one)
+        int32_t leading = 0, trailing = 0;
         for (int w = 0; w < 4; ++w) {
-            int32_t cnt = 0;
-            for (int32_t e = sb.n_kv[idx] - 1; e >= 0 && cnt < 255; --e) {
-                const int32_t info = sb.kv[2 * (static_cast<size_t>(sb.kv_first[idx]) + e) + 1];
-                if (((info >> (8 + 2 * w)) & 3) != 0) break;
-                ++cnt;
-            }
-            trailing |= cnt << (8 * w);
+            auto code = [&](int32_t e) {
+                return (sb.kv[2 * (static_cast<size_t>(sb.kv_first[idx]) + e) + 1] >> (8 + 2 * w)) & 3;
+            };
+            int32_t lead = 0, trail = 0;
+            while (lead < sb.n_kv[idx] && lead < 255 && code(lead) == 0) ++lead;
+            while (trail < sb.n_kv[idx] - lead && trail < 255 && code(sb.n_kv[idx] - 1 - trail) == 0) ++trail;
+            leading |= lead << (8 * w);
+            trailing |= trail << (8 * w);
         }
+        desc.push_back(leading);
         desc.push_back(trailing);
         rq.insert(rq.end(), sb.row_q.begin() + idx * BM, sb.row_q.begin() + (idx + 1) * BM);
         rlo.insert(rlo.end(), sb.row_lo.begin() + idx * BM, sb.row_lo.begin() + (idx + 1) * BM);
