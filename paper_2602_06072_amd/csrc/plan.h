@@ -53,7 +53,8 @@ struct DeviceTables {
     int32_t pad_split_tokens = 0, pad_n_splits = 0;   // padded decode comparison: uniform splits
     // prefill (packed and padded schedules share one format)
     struct PrefillSched {
-        TableRef tiles;             // [n_tiles][4] kv_first, n_kv, leading / trailing skipped key tiles per wave (4 x 8 bits each)
+        TableRef tiles;             // [n_tiles][8] kv_first, n_kv, leading / trailing skipped key tiles per wave (4 x 8 bits each),
+                                    // first Q row of a contiguous tile or -1, rows, 0, 0
         TableRef row_q, row_lo, row_hi;   // [n_tiles*BM]
         TableRef kvtiles;           // [n_kv_total][2] k_start, n | wavemask<<8 | full<<16
         int32_t n_tiles = 0;

@@ -67,7 +67,7 @@ __device__ __forceinline__ bool setup(const PrefillArgs& a, WorkUnit& u, LaneOff
     } else {
         tile = blockIdx.x / a.Hq; u.head = blockIdx.x % a.Hq; u.kvh = u.head / r;
     }
-    const int32_t* desc = a.tiles + 4 * static_cast<int64_t>(tile);
+    const int32_t* desc = a.tiles + 8 * static_cast<int64_t>(tile);
     u.n_kv = desc[1];
     if (u.n_kv == 0) return false;
     u.kvt = a.kvtiles + 2 * static_cast<int64_t>(desc[0]);
@@ -77,7 +77,11 @@ __device__ __forceinline__ bool setup(const PrefillArgs& a, WorkUnit& u, LaneOff
     u.n_active = u.n_kv - ((desc[3] >> (8 * u.wave)) & 0xFF);
     u.n_lead = min((desc[2] >> (8 * u.wave)) & 0xFF, u.n_active);
     const int rr = tile * BM + u.wave * 32 + u.n;
-    u.qrow = a.row_q[rr]; u.lo = a.row_lo[rr]; u.hi = a.row_hi[rr];
+    // a tile whose rows are one run of consecutive Q rows says so: no look-up ahead of the Q loads
+    const int q_first = desc[4], local = u.wave * 32 + u.n;
+    if (q_first >= 0) u.qrow = local < desc[5] ? q_first + local : -1;
+    else u.qrow = a.row_q[rr];
+    u.lo = a.row_lo[rr]; u.hi = a.row_hi[rr];
     u.row_bytes = static_cast<int64_t>(a.Hkv) * ROWB;
     u.row_bytes32 = static_cast<uint32_t>(a.Hkv) * ROWB;
     u.total_rows32 = static_cast<uint32_t>(a.total_kv_rows);

@@ -256,7 +256,7 @@ void emit_sched(const SchedBuild& sb, const std::vector<int32_t>& order, Builder
                 DeviceTables::PrefillSched& s) {
     constexpr int BM = kPrefillBM;
     std::vector<int32_t> desc, rq, rlo, rhi, kv;
-    desc.reserve(order.size() * 4);
+    desc.reserve(order.size() * 8);
     rq.reserve(sb.row_q.size()); rlo.reserve(sb.row_q.size()); rhi.reserve(sb.row_q.size());
     kv.reserve(sb.kv.size());
     for (int32_t idx : order) {
@@ -278,6 +278,15 @@ void emit_sched(const SchedBuild& sb, const std::vector<int32_t>& order, Builder
         }
         desc.push_back(leading);
         desc.push_back(trailing);
+        // the rows of most tiles are one run of consecutive rows of Q: then the kernel needs no
+        // row_q look-up before it can fetch its Q operand (first row, or -1 if they are not)
+        int32_t q_first = sb.n_rows[idx] > 0 ? sb.row_q[static_cast<size_t>(idx) * BM] : -1;
+        for (int32_t x = 0; x < sb.n_rows[idx] && q_first >= 0; ++x)
+            if (sb.row_q[static_cast<size_t>(idx) * BM + x] != q_first + x) q_first = -1;
+        desc.push_back(q_first);
+        desc.push_back(sb.n_rows[idx]);
+        desc.push_back(0);
+        desc.push_back(0);
         rq.insert(rq.end(), sb.row_q.begin() + idx * BM, sb.row_q.begin() + (idx + 1) * BM);
         rlo.insert(rlo.end(), sb.row_lo.begin() + idx * BM, sb.row_lo.begin() + (idx + 1) * BM);
         rhi.insert(rhi.end(), sb.row_hi.begin() + idx * BM, sb.row_hi.begin() + (idx + 1) * BM);
@@ -381,7 +390,7 @@ size_t padded_bound_bytes(const pk_plan& plan) {
             kv_entries += (ctx + std::min<int64_t>(plan.q_lens[i], (tt + 1) * BM) + BN - 1) / BN;
     }
     const int64_t tiles = max_tiles * plan.n;
-    const int64_t ints = tiles * 4 + 3 * tiles * BM + 2 * kv_entries + 6 * 64;
+    const int64_t ints = tiles * 8 + 3 * tiles * BM + 2 * kv_entries + 6 * 64;
     return static_cast<size_t>((ints + 63) / 64 * 64) * sizeof(int32_t);
 }
 
