@@ -263,6 +263,57 @@ def capacity_sweep(wl, pk, seed, dev):
     return rows
 
 
+def motivation_replay(wl, pk, seed, dev):
+    """Analogue of the paper's motivation experiment (Sec. 2.2, heterogeneous against homogeneous
+    batches with the same number of requests and the same total tokens), plus a mix in which more
+    than 60 % of the requests are shorter than 128 tokens (Sec. 3.1).  Prefill layer time, packed
+    and padded, and one decode step, packed and padded."""
+    import torch
+    rng = np.random.default_rng(seed + 77)
+    het = wl.config2_lengths(seed)
+    n, total = len(het), int(het.sum())
+    hom = np.full(n, total // n, dtype=np.int32)
+    hom[: total - int(hom.sum())] += 1
+    # skewed mix: 70 % of the requests uniform in [8, 127], the rest share the remaining tokens
+    n_short = int(0.7 * n)
+    short = rng.integers(8, 128, size=n_short).astype(np.int32)
+    rest = total - int(short.sum())
+    wts = np.exp(rng.normal(0.0, 1.0, size=n - n_short))
+    longs = np.maximum(128, np.floor(wts / wts.sum() * rest)).astype(np.int32)
+    longs[0] += rest - int(longs.sum())
+    skew = rng.permutation(np.concatenate([short, longs])).astype(np.int32)
+    res = {}
+    for name, lens in (("homogeneous", hom), ("heterogeneous_cfg2", het), ("skewed_70pct_under_128", skew)):
+        w = wl.make_ragged(name, lens, lens, 32, 8, 128, 16384, seed, dev)
+        plan = pk.pack_plan(w.kv_lens, w.q_lens, token_budget=w.token_budget)
+        ws = pk.new_workspace(plan, w.Hq, w.Hkv, w.d, pk.PK_BF16)
+        pk.plan_bind(plan, w.Hq, w.Hkv, w.d, pk.PK_BF16, ws)
+        out = torch.empty(w.q.shape, dtype=torch.bfloat16, device=dev)
+        pk_ms, _ = _time_launches(lambda: pk.packed_prefill_attn(plan, w.q, w.k, w.v, out, w.scale, ws), 20)
+        pd_ms, _ = _time_launches(lambda: pk.padded_prefill_attn(plan, w.q, w.k, w.v, out, w.scale, ws), 20)
+        row = {"requests": int(n), "tokens": int(lens.sum()), "max_len": int(lens.max()),
+               "share_under_128": float((lens < 128).mean()),
+               "prefill_packed_ms": pk_ms, "prefill_padded_ms": pd_ms,
+               "prefill_useful_over_issued_packed": plan.stat(0) / max(1, plan.stat(1)),
+               "prefill_useful_over_issued_padded": plan.stat(0) / max(1, plan.stat(2))}
+        del w, out, ws
+        wd = wl.make_paged(name, lens, 32, 8, 128, 16384, 16, seed, device=dev)
+        ones = np.ones_like(wd.kv_lens)
+        pland = pk.pack_plan(wd.kv_lens, ones, None, None, wd.token_budget)
+        wsd = pk.new_workspace(pland, wd.Hq, wd.Hkv, wd.d, pk.PK_BF16)
+        pk.plan_bind(pland, wd.Hq, wd.Hkv, wd.d, pk.PK_BF16, wsd)
+        buf = pk.new_kv_buf(pland, wd.Hkv, wd.d, pk.PK_BF16)
+        bt = torch.from_numpy(wd.block_table).to(dev)
+        pk.kv_reorganize(pland, wd.k_pages, wd.v_pages, bt, buf, wsd)
+        outd = torch.empty(wd.q.shape, dtype=torch.bfloat16, device=dev)
+        d_ms, _ = _time_launches(lambda: pk.packed_decode_attn(pland, wd.q, buf, outd, wd.scale, wd.Hkv, wsd), 20)
+        p_ms, _ = _time_launches(lambda: pk.padded_decode_attn(pland, wd.q, wd.k_pages, wd.v_pages, bt, outd, wd.scale, wsd), 20)
+        row.update({"decode_packed_ms": d_ms, "decode_padded_ms": p_ms})
+        res[name] = row
+        del wd, buf, wsd, outd
+    return res
+
+
 def cpu_baseline(w):
     """The oracle as it stands, timed on every second query row of the batch."""
     from oracle import attention as oa
@@ -301,6 +352,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain elementwise kernel over 1 GiB 5 times (reference for HBM byte counters)")
+    ap.add_argument("--motivation", action="store_true",
+                    help="instead of the benchmark line: homogeneous / heterogeneous / skewed batches of equal size (one JSON line)")
     ap.add_argument("--capacity-sweep", action="store_true",
                     help="instead of the benchmark line: profile the group capacity C over a range (one JSON line)")
     args = ap.parse_args()
@@ -319,6 +372,9 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
 
+    if args.motivation:
+        print(json.dumps({"motivation_replay": motivation_replay(wl, pk, args.seed, dev), "seed": args.seed}))
+        return
     if args.capacity_sweep:
         print(json.dumps({"capacity_sweep": capacity_sweep(wl, pk, args.seed, dev), "seed": args.seed,
                           "workloads": "configs[1] prefill, configs[2] decode"}))

@@ -310,6 +310,20 @@ void build_prefill_packed(const pk_plan& plan, const std::vector<int64_t>& q_sta
     for (const Group& g : plan.groups) {
         rows.clear();
         for (const Member& m : g.members) {
+            // A request that does not fit into what is left of the current tile shares it only if
+            // that saves the request a tile of its own (its head then rides along with few key
+            // tiles); otherwise the tile is closed and the request starts on a fresh one: a shared
+            // tile walks the key tiles of both requests one after the other and runs them masked.
+            const int32_t lq = plan.q_lens[m.req];
+            const int32_t room = BM - static_cast<int32_t>(rows.size());
+            if (!rows.empty() && lq > room) {
+                const int32_t last = lq % BM == 0 ? BM : lq % BM;   // rows of its last tile when it starts fresh
+                if (room < last) {
+                    tile_req.push_back(rows[0].req);
+                    add_tile(plan, q_start, kv_start, rows.data(), static_cast<int>(rows.size()), false, sb);
+                    rows.clear();
+                }
+            }
             for (int32_t x = 0; x < plan.q_lens[m.req]; ++x) {
                 rows.push_back({m.req, x});
                 if (rows.size() == BM) {
