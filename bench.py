@@ -41,12 +41,19 @@ def _events(n):
     return [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
 
 
-def _time_launches(fn, iters, warmup=3):
-    """Average duration (ms) of fn's device work, one event pair per launch."""
+def _time_launches(fn, iters, warmup=3, warm_ms=40.0):
+    """Average duration (ms) of fn's device work, one event pair per launch.  The GPU clock keeps
+    rising for tens of milliseconds after idle, so fn is first repeated for at least warm_ms:
+    whichever of two kernels is timed first is otherwise at a disadvantage."""
     import torch
     for _ in range(warmup):
         fn()
     torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    while (time.perf_counter() - t0) * 1e3 < warm_ms:
+        for _ in range(4):
+            fn()
+        torch.cuda.synchronize()
     ev = _events(iters)
     for a, b in ev:
         a.record()
@@ -345,8 +352,8 @@ def profiled_traffic(tag):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-extras", action="store_true", help="skip the decode / mixed-step lines")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
