@@ -295,12 +295,14 @@ __device__ __forceinline__ void pin_slice_outputs(bf16x8& next_operand, HalfSoft
     }
 }
 
-// -inf for the keys of half `half` of a tile that a query row may not see (outside [lo, hi_t))
+// -inf for the keys of half `half` of a tile that a query row may not see (outside [lo, hi_t)):
+// one unsigned comparison per score, (key - lo) < (hi_t - lo).
 __device__ __forceinline__ void mask_half(floatx16& s, int half, int lo, int hi_t, int k_start, int hlf) {
+    const uint32_t span = static_cast<uint32_t>(max(hi_t - lo, 0));
+    const uint32_t base = static_cast<uint32_t>(k_start + 4 * hlf + 32 * half - lo);
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
-        const int key = k_start + 32 * half + 8 * (e >> 2) + 4 * hlf + (e & 3);
-        if (key < lo || key >= hi_t) s[e] = -INFINITY;
+        if (base + static_cast<uint32_t>(8 * (e >> 2) + (e & 3)) >= span) s[e] = -INFINITY;
         asm volatile("" : "+v"(s[e]));   // ties the selects to this place, behind the caller's branch
     }
 }
