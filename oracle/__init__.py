@@ -18,5 +18,7 @@ Modules:
                Eq. 4 (pinned by hand-worked examples and a brute force of the
                definition); the cadence the paper mentions for its own
                workloads (every 20-40 steps) is "parity unpinned".
+  trie      -- TriePartition from token ids: the one-level choice of shared prefixes that
+               minimises Eq. 5; pinned (hand-worked examples, exhaustive search on tiny inputs).
   paged.append_step -- the headroom slot a generated token goes to (Sec. 3.2); pinned.
 """
