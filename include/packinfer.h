@@ -193,6 +193,27 @@ int pk_packed_decode_attn(pk_plan* plan, const void* q, const void* kv_buf,
                           void* workspace, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------
+ * pk_trie_partition -- TriePartition of Alg. 1 Part 2 from token ids (Sec.
+ * 3.2: the requests of a batch form a prefix tree whose common prefixes are
+ * stored once).  Produces the prefix_ids / prefix_lens that pk_pack_plan
+ * takes: every request is assigned to at most one shared prefix, a prefix
+ * has at least min_prefix tokens and at least two requests, and among all
+ * such assignments the one with the largest saving sum d_k * (m_k - 1) is
+ * returned (d_k tokens shared by m_k requests: the reduction of Eq. 5); on a
+ * tie between a prefix and the prefixes nested below it the outer one wins.
+ * Families are numbered by their lowest request index.  Host only.
+ *
+ *   token_ids     host, the n token sequences one after the other
+ *   kv_lens       host [n], length of each sequence (> 0)
+ *   prefix_ids    host [n] out: family or -1     prefix_lens  host [n] out
+ *   saved_tokens  optional out: the saving
+ * Errors: PK_EINVAL (NULL, n < 0, min_prefix < 1, kv_len <= 0).
+ */
+int pk_trie_partition(const int32_t* token_ids, const int32_t* kv_lens, int32_t n,
+                      int32_t min_prefix, int32_t* prefix_ids, int32_t* prefix_lens,
+                      int64_t* saved_tokens);
+
+/* ------------------------------------------------------------------------
  * Decoding over several steps with one plan (Sec. 3.2: every suffix is
  * allocated L_Q + delta tokens, "which reserves space for future token
  * generation"; Sec. 3.1 "Adaptive Grouping", Eq. 4: when to regroup).

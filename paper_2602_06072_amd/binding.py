@@ -72,6 +72,8 @@ def lib():
     L.pk_kv_append.argtypes = [vp, vp, vp, vp, i32, ci, ci, ci, vp, sz, vp]
     L.pk_regroup_due.restype = ci
     L.pk_regroup_due.argtypes = [vp, i32, ctypes.POINTER(i32), ctypes.POINTER(i64)]
+    L.pk_trie_partition.restype = ci
+    L.pk_trie_partition.argtypes = [vp, vp, i32, i32, vp, vp, ctypes.POINTER(i64)]
     L.pk_plan_stat.restype = i64
     L.pk_plan_stat.argtypes = [vp, ci]
     L.pk_last_error.restype = ctypes.c_char_p
@@ -86,7 +88,7 @@ EXPORTS = [
     "pk_plan_serialize", "pk_kv_buf_bytes", "pk_workspace_bytes", "pk_plan_bind",
     "pk_kv_reorganize", "pk_packed_prefill_attn", "pk_packed_decode_attn",
     "pk_padded_prefill_attn", "pk_padded_decode_attn", "pk_plan_stat", "pk_last_error",
-    "pk_kv_append", "pk_packed_decode_attn_grown", "pk_regroup_due",
+    "pk_kv_append", "pk_packed_decode_attn_grown", "pk_regroup_due", "pk_trie_partition",
 ]
 REGROUP_DRIFT, REGROUP_HEADROOM, REGROUP_DRIFT_WITHIN_BUDGET = 1, 2, 4
 
@@ -275,6 +277,21 @@ def kv_append(plan, k_new, v_new, kv_buf, step, workspace, stream=None):
         _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
     _check(rc, "pk_kv_append")
     return kv_buf
+
+
+def trie_partition(seqs, min_prefix=1):
+    """seqs: list of token-id sequences.  Returns (prefix_ids, prefix_lens, saved_tokens)."""
+    n = len(seqs)
+    lens = np.asarray([len(s) for s in seqs], dtype=np.int32)
+    flat = np.ascontiguousarray(np.concatenate([np.asarray(s, dtype=np.int32) for s in seqs]) if n else
+                                np.zeros(0, dtype=np.int32))
+    ids = np.full(n, -1, dtype=np.int32)
+    plens = np.zeros(n, dtype=np.int32)
+    saved = ctypes.c_int64(0)
+    rc = lib().pk_trie_partition(flat.ctypes.data, lens.ctypes.data, n, int(min_prefix),
+                                 ids.ctypes.data, plens.ctypes.data, ctypes.byref(saved))
+    _check(rc, "pk_trie_partition")
+    return ids, plens, saved.value
 
 
 def regroup_due(plan, steps):

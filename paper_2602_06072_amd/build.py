@@ -12,7 +12,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(CSRC, "_build")
 LIB = os.path.join(HERE, "libpackinfer.so")
 
-SOURCES = ["planner.cpp", "schedule.cpp", "api.cpp", "debug_f32.hip", "reorg.hip",
+SOURCES = ["planner.cpp", "schedule.cpp", "api.cpp", "trie.cpp", "debug_f32.hip", "reorg.hip",
            "decode.hip", "prefill.hip", "prefill_pipe.hip", "padded_decode.hip"]
 
 HIP_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

@@ -186,3 +186,54 @@ def test_step_entry_points_validate_before_touching_the_device():
     assert L.pk_packed_decode_attn_grown(plan.handle, p, p, p, 1.0, 3, 4, 2, 64, 0, 0, p, 16, None) == -1   # grown > headroom
     prefill_plan = pk.pack_plan([4, 4], token_budget=8, headroom=2)
     assert L.pk_kv_append(prefill_plan.handle, p, p, p, 0, 2, 64, 0, p, 16, None) == -1   # not a decode plan
+
+
+# ---- TriePartition from token ids: host logic, bit-equal to the oracle ----------------------------
+from oracle import trie as otrie  # noqa: E402
+
+
+@settings(max_examples=500, deadline=None)
+@given(st.lists(st.lists(st.integers(0, 3), min_size=1, max_size=12), min_size=0, max_size=14), st.integers(1, 4))
+def test_trie_partition_equals_oracle(seqs, min_prefix):
+    ids, lens, saved = pk.trie_partition(seqs, min_prefix)
+    want = otrie.trie_partition(seqs, min_prefix)
+    assert list(ids) == want[0] and list(lens) == want[1] and saved == want[2]
+
+
+def test_trie_partition_on_a_config4_shaped_batch_feeds_the_planner():
+    w = wl.config4(0)
+    rng = np.random.default_rng(5)
+    fam_tokens = {}
+    seqs = []
+    for i in range(w.n):
+        f, lp, L = int(w.prefix_ids[i]), int(w.prefix_lens[i]), int(w.kv_lens[i])
+        if f >= 0 and f not in fam_tokens:
+            fam_tokens[f] = rng.integers(0, 32000, size=lp)
+        head = fam_tokens[f] if f >= 0 else np.zeros(0, dtype=np.int64)
+        # the first private token is made unique so that the shared part is exactly the family prefix
+        tail = np.concatenate([[100000 + i], rng.integers(0, 32000, size=L - lp - 1)]) if L > lp else np.zeros(0, dtype=np.int64)
+        seqs.append(np.concatenate([head, tail]).astype(np.int32))
+    ids, lens, saved = pk.trie_partition(seqs)
+    want = otrie.trie_partition([list(s) for s in seqs])
+    assert list(ids) == want[0] and list(lens) == want[1] and saved == want[2]
+    # the families of the generator come back (up to numbering)
+    assert np.array_equal(lens, np.where(w.prefix_ids >= 0, w.prefix_lens, 0))
+    for f in set(int(x) for x in w.prefix_ids if x >= 0):
+        members = np.where(w.prefix_ids == f)[0]
+        assert len(set(ids[members])) == 1 and ids[members[0]] >= 0
+    ones = np.ones(w.n, dtype=np.int32)
+    a = pk.pack_plan(w.kv_lens, ones, ids, lens, w.token_budget)
+    b = pk.pack_plan(w.kv_lens, ones, w.prefix_ids, w.prefix_lens, w.token_budget)
+    assert a.unique_tokens == b.unique_tokens == int(w.kv_lens.sum()) - saved
+
+
+def test_trie_partition_error_paths():
+    L = pk.lib()
+    one = np.array([1], dtype=np.int32)
+    out = np.zeros(1, dtype=np.int32)
+    assert L.pk_trie_partition(None, None, 0, 1, None, None, None) == 0                 # empty batch
+    assert L.pk_trie_partition(None, one.ctypes.data, 1, 1, out.ctypes.data, out.ctypes.data, None) == -1
+    assert L.pk_trie_partition(one.ctypes.data, one.ctypes.data, 1, 0, out.ctypes.data, out.ctypes.data, None) == -1
+    zero = np.array([0], dtype=np.int32)
+    assert L.pk_trie_partition(one.ctypes.data, zero.ctypes.data, 1, 1, out.ctypes.data, out.ctypes.data, None) == -1
+    assert L.pk_trie_partition(one.ctypes.data, one.ctypes.data, -1, 1, out.ctypes.data, out.ctypes.data, None) == -1
