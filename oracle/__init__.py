@@ -20,5 +20,8 @@ Modules:
                workloads (every 20-40 steps) is "parity unpinned".
   trie      -- TriePartition from token ids: the one-level choice of shared prefixes that
                minimises Eq. 5; pinned (hand-worked examples, exhaustive search on tiny inputs).
+  planner.make_plan_tree, paged.group_buffer_tree, trie.trie_tree -- nested shared prefixes
+               (a forest of segments): plan, dense buffer and the whole-tree TriePartition; pinned
+               (hand-worked words, invariants, reduction to the one-level plan).
   paged.append_step -- the headroom slot a generated token goes to (Sec. 3.2); pinned.
 """

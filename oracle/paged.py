@@ -55,3 +55,29 @@ def append_step(buf, members, step, new_rows):
     for (req, _poff, _lp, soff, lq) in members:
         buf[soff + lq + step] = new_rows[req]
     return buf
+
+
+def group_buffer_tree(pages, block_table, page_size, nodes, members, total_tokens, fill):
+    """Dense buffer of a group whose shared prefixes form a forest: every node's segment once
+    (taken from the lowest-index request below it), then the private suffixes.
+
+    nodes: (node id, off, len, parent local or -1); members: (req, node local or -1, suffix_off,
+    L_Q) as in the tree plan.  Returns [total_tokens, Hkv, d]."""
+    buf = np.full((total_tokens,) + tuple(pages.shape[2:]), fill, dtype=pages.dtype)
+    start = []                                       # logical position at which a node's segment begins
+    for (_, off, ln, par) in nodes:
+        start.append(0 if par < 0 else start[par] + nodes[par][2])
+    owner = [None] * len(nodes)                      # lowest request below each node
+    for (req, node, soff, lq) in members:
+        k = node
+        while k >= 0:
+            owner[k] = req if owner[k] is None else min(owner[k], req)
+            k = nodes[k][3]
+    for k, (_, off, ln, par) in enumerate(nodes):
+        full = logical_kv(pages, block_table[owner[k]], start[k] + ln, page_size)
+        buf[off:off + ln] = full[start[k]:start[k] + ln]
+    for (req, node, soff, lq) in members:
+        shared = 0 if node < 0 else start[node] + nodes[node][2]
+        full = logical_kv(pages, block_table[req], shared + lq, page_size)
+        buf[soff:soff + lq] = full[shared:shared + lq]
+    return buf

@@ -181,3 +181,143 @@ def headroom_exhausted(plan: Plan, t: int) -> bool:
     """After t appended tokens per request a further one has no slot left (Sec. 3.2: every suffix
     is allocated L_Q + delta tokens)."""
     return t >= plan.headroom
+
+
+# ---- nested prefixes: a forest of shared segments (Sec. 3.2, prefix tree T_g; Eq. 5) -----------
+@dataclass
+class TreeGroup:
+    load: int = 0
+    buf_tokens: int = 0
+    buf_base: int = 0
+    nodes: List[Tuple[int, int, int, int]] = field(default_factory=list)    # (node id, off, len, parent local or -1)
+    members: List[Tuple[int, int, int, int]] = field(default_factory=list)  # (req, node local or -1, suffix_off, L_Q)
+
+
+@dataclass
+class TreePlan:
+    n: int
+    token_budget: int
+    headroom: int
+    groups: List[TreeGroup]
+    total_buf_tokens: int
+
+    def words(self) -> List[int]:
+        def lohi(x):
+            return [x & 0xFFFFFFFF, (x >> 32) & 0xFFFFFFFF]
+        w = [MAGIC, 2, self.n, len(self.groups)] + lohi(self.token_budget)
+        w += [self.headroom, GROUP_ALIGN] + lohi(self.total_buf_tokens)
+        for g in self.groups:
+            w += lohi(g.load) + lohi(g.buf_tokens) + lohi(g.buf_base) + [len(g.nodes), len(g.members)]
+            for nd in g.nodes:
+                w += list(nd)
+            for m in g.members:
+                w += list(m)
+        return [x - (1 << 32) if x >= (1 << 31) else x for x in w]
+
+
+def make_plan_tree(kv_lens: Sequence[int], q_lens: Optional[Sequence[int]],
+                   node_parent: Sequence[int], node_len: Sequence[int], req_node: Sequence[int],
+                   token_budget: int = 8192, headroom: int = 0) -> TreePlan:
+    """Alg. 1 with the shared prefixes given as a forest: node k is a segment of node_len[k] tokens
+    that follows its parent's segment (node_parent[k] < k, or -1 for a root); request i continues
+    after node req_node[i] (-1: it shares nothing).  The unique tokens of a tree are counted once
+    (Eq. 5 applied at every level); a tree is one atomic item of the greedy assignment; inside a
+    group a tree is laid out parent first: the node's segment, then the suffixes of the requests
+    attached to it (ascending request index, each followed by the headroom), then its child nodes
+    (ascending node index)."""
+    kv_lens = [int(x) for x in kv_lens]
+    n, m, C = len(kv_lens), len(node_len), int(token_budget)
+    if C <= 0 or headroom < 0:
+        raise PlanError("budget must be positive and headroom non-negative")
+    depth = [0] * m
+    for k in range(m):
+        if node_len[k] <= 0 or not (-1 <= node_parent[k] < k):
+            raise PlanError("node_len must be positive and node_parent[k] in [-1, k)")
+        depth[k] = node_len[k] + (depth[node_parent[k]] if node_parent[k] >= 0 else 0)
+    direct = [[] for _ in range(m)]
+    for i in range(n):
+        if kv_lens[i] <= 0 or (q_lens is not None and not (0 < q_lens[i] <= kv_lens[i])):
+            raise PlanError("bad lengths")
+        k = int(req_node[i])
+        if not (-1 <= k < m) or (k >= 0 and depth[k] > kv_lens[i]):
+            raise PlanError("req_node out of range or deeper than the request")
+        if k >= 0:
+            direct[k].append(i)
+    kids = [[] for _ in range(m)]
+    for k in range(m):
+        if node_parent[k] >= 0:
+            kids[node_parent[k]].append(k)
+
+    def below(k):                                   # requests in the subtree of node k
+        out = list(direct[k])
+        for c in kids[k]:
+            out += below(c)
+        return out
+
+    def tree_nodes(k):
+        out = [k]
+        for c in kids[k]:
+            out += tree_nodes(c)
+        return out
+
+    for k in range(m):
+        if not below(k):
+            raise PlanError("a node without requests below it")
+
+    def shared(i):
+        return depth[req_node[i]] if req_node[i] >= 0 else 0
+
+    items = []                                      # (length, first member, root or -1, members)
+    for i in range(n):
+        if req_node[i] < 0:
+            items.append((kv_lens[i], i, -1, [i]))
+    for k in range(m):
+        if node_parent[k] < 0:
+            mem = sorted(below(k))
+            length = sum(node_len[x] for x in tree_nodes(k)) + sum(kv_lens[i] - shared(i) for i in mem)
+            items.append((length, mem[0], k, mem))
+
+    l_total = sum(it[0] for it in items)
+    G = -(-l_total // C)
+    loads = [0] * G
+    assigned = [[] for _ in range(G)]
+    for it in sorted(items, key=lambda it: (-it[0], it[1])):
+        g = min(range(len(loads)), key=lambda j: (loads[j], j)) if loads else -1
+        if g >= 0 and loads[g] + it[0] <= C:
+            loads[g] += it[0]
+            assigned[g].append(it)
+        else:
+            loads.append(it[0])
+            assigned.append([it])
+
+    groups, base = [], 0
+    for load, its in zip(loads, assigned):
+        if not its:
+            continue
+        g = TreeGroup(load=load)
+        delta = 0
+        local = {}
+
+        def place(k):
+            nonlocal delta
+            local[k] = len(g.nodes)
+            g.nodes.append((k, delta, node_len[k], local[node_parent[k]] if node_parent[k] >= 0 else -1))
+            delta += node_len[k]
+            for i in sorted(direct[k]):
+                lq = kv_lens[i] - depth[k]
+                g.members.append((i, local[k], delta, lq))
+                delta += lq + headroom
+            for c in kids[k]:
+                place(c)
+
+        for (_, first, root, mem) in its:
+            if root < 0:
+                g.members.append((first, -1, delta, kv_lens[first]))
+                delta += kv_lens[first] + headroom
+            else:
+                place(root)
+        g.buf_tokens = delta
+        g.buf_base = base
+        base = -(-(base + delta) // GROUP_ALIGN) * GROUP_ALIGN
+        groups.append(g)
+    return TreePlan(n, C, int(headroom), groups, base)

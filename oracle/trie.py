@@ -63,3 +63,55 @@ def trie_partition(seqs: Sequence[Sequence[int]], min_prefix: int = 1) -> Tuple[
         for i in members:
             ids[i], lens[i] = fam, depth
     return ids, lens, saved
+
+
+def trie_tree(seqs: Sequence[Sequence[int]], min_prefix: int = 1):
+    """The whole prefix tree of a batch as a forest of shared segments (all levels kept): a node
+    for every tree node below which at least two requests lie and whose depth is at least
+    min_prefix; chains without branching are one segment.  Returns (node_parent, node_len,
+    req_node, saved_tokens); nodes are numbered by (lowest request below, depth), so a parent has
+    a smaller number than its children; req_node[i] is the deepest node above request i or -1.
+    The saving is sum over nodes of node_len * (requests below - 1): Eq. 5 applied at every level."""
+    import sys
+    n = len(seqs)
+    min_prefix = max(1, int(min_prefix))
+    raw = []                                         # (first request, depth, members, parent depth key)
+
+    def walk(members, depth, parent_key):
+        while True:
+            if any(len(seqs[i]) == depth for i in members):
+                break
+            if len({seqs[i][depth] for i in members}) != 1:
+                break
+            depth += 1
+        key = parent_key
+        if depth >= min_prefix and len(members) >= 2:
+            key = (min(members), depth)
+            raw.append((key, parent_key, sorted(members)))
+        children = {}
+        for i in members:
+            if len(seqs[i]) > depth:
+                children.setdefault(seqs[i][depth], []).append(i)
+        for tok in sorted(children):
+            if len(children[tok]) >= 2:
+                walk(children[tok], depth + 1, key)
+
+    old = sys.getrecursionlimit()
+    sys.setrecursionlimit(max(old, 10000))
+    try:
+        if n >= 2:
+            walk(list(range(n)), 0, None)
+    finally:
+        sys.setrecursionlimit(old)
+    raw.sort(key=lambda r: r[0])
+    number = {r[0]: k for k, r in enumerate(raw)}
+    node_parent, node_len, req_node, saved = [], [], [-1] * n, 0
+    for k, (key, pkey, members) in enumerate(raw):
+        pdepth = pkey[1] if pkey is not None else 0
+        node_parent.append(number[pkey] if pkey is not None else -1)
+        node_len.append(key[1] - pdepth)
+        saved += (key[1] - pdepth) * (len(members) - 1)
+        for i in members:                            # deeper nodes come later in the numbering
+            if req_node[i] < 0 or raw[req_node[i]][0][1] < key[1]:
+                req_node[i] = k
+    return node_parent, node_len, req_node, saved
