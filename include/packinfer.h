@@ -80,6 +80,34 @@ int pk_pack_plan(const int32_t* kv_lens, const int32_t* q_lens,
                  const int32_t* prefix_ids, const int32_t* prefix_lens,
                  int32_t n, int64_t token_budget, int32_t headroom, pk_plan** out);
 
+/* pk_pack_plan_tree -- the same planner for NESTED shared prefixes (Sec. 3.2
+ * "Prefix-Aware Grouping and Reuse": TriePartition yields shared prefixes at
+ * every level of the prefix tree; Eq. 5 counts each shared segment once).
+ * The prefixes are given as a forest of segments:
+ *   node_parent host [n_nodes]  parent of node k, in [-1, k) (-1: a root)
+ *   node_len    host [n_nodes]  tokens of the segment, > 0; a node stands for
+ *                               the tokens [depth(parent), depth(parent)+len)
+ *                               of every request below it
+ *   req_node    host [n]        deepest node above request i, or -1; the
+ *                               request's own suffix is what follows
+ *                               depth(req_node[i]) (it may be empty)
+ *   kv_lens, q_lens, token_budget, headroom, out: as for pk_pack_plan.
+ * Every node needs at least one request below it.  The caller guarantees
+ * that requests below a node hold identical K/V on that segment.
+ * Grouping: a whole tree is one atomic item of length sum(node_len) +
+ * sum(suffixes) and is never cut (a tree above C is alone in its group);
+ * otherwise as pk_pack_plan.  Layout inside a group, per tree in pre-order:
+ * the node's segment, the suffixes (+ headroom) of the requests attached
+ * directly to it in ascending order, then its children in ascending order.
+ * pk_trie_tree produces this input from token ids.  A forest of roots only
+ * gives the layout of pk_pack_plan with uncut families.
+ * Errors: PK_EINVAL for any violated precondition.
+ */
+int pk_pack_plan_tree(const int32_t* kv_lens, const int32_t* q_lens, int32_t n,
+                      const int32_t* node_parent, const int32_t* node_len, int32_t n_nodes,
+                      const int32_t* req_node, int64_t token_budget, int32_t headroom,
+                      pk_plan** out);
+
 void pk_plan_destroy(pk_plan* plan);
 
 /* Read-only accessors (host). */
@@ -99,6 +127,11 @@ int64_t pk_plan_unique_tokens(const pk_plan* plan);
  *   member (layout order): request, prefix_off, L_P, suffix_off, L_Q
  *   (offsets in tokens relative to the group base) -- the tuple O_g[i] of
  *   Alg. 1.
+ * A plan of pk_pack_plan_tree has version 2 and per group, after buf_base:
+ *   n_nodes, n_members, then per node (layout order): caller's node number,
+ *   offset, tokens, parent (index among the group's nodes or -1), then per
+ *   member (layout order): request, node (index among the group's nodes or
+ *   -1), suffix_off, suffix tokens.
  * pk_plan_serialized_words returns the word count; pk_plan_serialize copies
  * them to host `out` (capacity `cap` words) and returns the count or
  * PK_EINVAL if cap is too small. */
@@ -212,6 +245,26 @@ int pk_packed_decode_attn(pk_plan* plan, const void* q, const void* kv_buf,
 int pk_trie_partition(const int32_t* token_ids, const int32_t* kv_lens, int32_t n,
                       int32_t min_prefix, int32_t* prefix_ids, int32_t* prefix_lens,
                       int64_t* saved_tokens);
+
+/* pk_trie_tree -- the whole prefix tree of a batch as the forest of shared
+ * segments pk_pack_plan_tree takes (Sec. 3.2; Eq. 5 at every level: a segment
+ * of len tokens above m requests saves len * (m - 1) tokens).  A node is made
+ * for every branching point of the tree (or end of a request) below which at
+ * least two requests lie and whose depth is at least min_prefix; runs without
+ * branching are one segment.  Host only.
+ *   token_ids, kv_lens, n, min_prefix: as for pk_trie_partition
+ *   node_parent, node_len host [n] out: the first *n_nodes entries are set
+ *                         (there are at most n - 1 nodes)
+ *   n_nodes     host out
+ *   req_node    host [n] out: deepest node above request i or -1
+ *   saved_tokens host out (may be NULL)
+ * Nodes are numbered by (lowest request below, depth), so parents precede
+ * children and the output does not depend on the sort inside.
+ * Errors: PK_EINVAL for any violated precondition.
+ */
+int pk_trie_tree(const int32_t* token_ids, const int32_t* kv_lens, int32_t n,
+                 int32_t min_prefix, int32_t* node_parent, int32_t* node_len,
+                 int32_t* n_nodes, int32_t* req_node, int64_t* saved_tokens);
 
 /* ------------------------------------------------------------------------
  * Decoding over several steps with one plan (Sec. 3.2: every suffix is

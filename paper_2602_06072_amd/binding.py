@@ -72,6 +72,10 @@ def lib():
     L.pk_kv_append.argtypes = [vp, vp, vp, vp, i32, ci, ci, ci, vp, sz, vp]
     L.pk_regroup_due.restype = ci
     L.pk_regroup_due.argtypes = [vp, i32, ctypes.POINTER(i32), ctypes.POINTER(i64)]
+    L.pk_pack_plan_tree.restype = ci
+    L.pk_pack_plan_tree.argtypes = [vp, vp, i32, vp, vp, i32, vp, i64, i32, ctypes.POINTER(vp)]
+    L.pk_trie_tree.restype = ci
+    L.pk_trie_tree.argtypes = [vp, vp, i32, i32, vp, vp, ctypes.POINTER(i32), vp, ctypes.POINTER(i64)]
     L.pk_trie_partition.restype = ci
     L.pk_trie_partition.argtypes = [vp, vp, i32, i32, vp, vp, ctypes.POINTER(i64)]
     L.pk_plan_stat.restype = i64
@@ -89,6 +93,7 @@ EXPORTS = [
     "pk_kv_reorganize", "pk_packed_prefill_attn", "pk_packed_decode_attn",
     "pk_padded_prefill_attn", "pk_padded_decode_attn", "pk_plan_stat", "pk_last_error",
     "pk_kv_append", "pk_packed_decode_attn_grown", "pk_regroup_due", "pk_trie_partition",
+    "pk_pack_plan_tree", "pk_trie_tree",
 ]
 REGROUP_DRIFT, REGROUP_HEADROOM, REGROUP_DRIFT_WITHIN_BUDGET = 1, 2, 4
 
@@ -199,6 +204,19 @@ def pack_plan(kv_lens: Sequence[int], q_lens: Optional[Sequence[int]] = None,
     return Plan(h.value)
 
 
+def pack_plan_tree(kv_lens: Sequence[int], q_lens: Optional[Sequence[int]],
+                   node_parent: Sequence[int], node_len: Sequence[int], req_node: Sequence[int],
+                   token_budget: int = 8192, headroom: int = 0) -> Plan:
+    kv, ql, par, nl, rn = _i32(kv_lens), _i32(q_lens), _i32(node_parent), _i32(node_len), _i32(req_node)
+    if (ql is not None and ql.shape != kv.shape) or rn.shape != kv.shape or par.shape != nl.shape:
+        raise PackInferError("pack_plan_tree: array lengths differ")
+    h = ctypes.c_void_p()
+    rc = lib().pk_pack_plan_tree(_ptr(kv), _ptr(ql), kv.shape[0], _ptr(par), _ptr(nl), par.shape[0],
+                                 _ptr(rn), int(token_budget), int(headroom), ctypes.byref(h))
+    _check(rc, "pk_pack_plan_tree")
+    return Plan(h.value)
+
+
 def new_workspace(plan: Plan, Hq, Hkv, d, dtype, device="cuda"):
     import torch
     nbytes = max(256, plan.workspace_bytes(Hq, Hkv, d, dtype))
@@ -292,6 +310,22 @@ def trie_partition(seqs, min_prefix=1):
                                  ids.ctypes.data, plens.ctypes.data, ctypes.byref(saved))
     _check(rc, "pk_trie_partition")
     return ids, plens, saved.value
+
+
+def trie_tree(seqs, min_prefix=1):
+    """seqs: list of token-id sequences.  Returns (node_parent, node_len, req_node, saved_tokens)."""
+    n = len(seqs)
+    lens = np.asarray([len(s) for s in seqs], dtype=np.int32)
+    flat = np.ascontiguousarray(np.concatenate([np.asarray(s, dtype=np.int32) for s in seqs]) if n else
+                                np.zeros(0, dtype=np.int32))
+    par = np.zeros(max(n, 1), dtype=np.int32)
+    nl = np.zeros(max(n, 1), dtype=np.int32)
+    rn = np.full(n, -1, dtype=np.int32)
+    nn, saved = ctypes.c_int32(0), ctypes.c_int64(0)
+    rc = lib().pk_trie_tree(flat.ctypes.data, lens.ctypes.data, n, int(min_prefix), par.ctypes.data,
+                            nl.ctypes.data, ctypes.byref(nn), rn.ctypes.data, ctypes.byref(saved))
+    _check(rc, "pk_trie_tree")
+    return par[:nn.value].copy(), nl[:nn.value].copy(), rn, saved.value
 
 
 def regroup_due(plan, steps):

@@ -245,6 +245,7 @@ int decode_common(const char* who, pk_plan* plan, const void* q, const void* kv_
     a.members = tab(plan, t.dec_members); a.member_slot = tab(plan, t.dec_member_slot);
     a.req_part_start = tab(plan, t.dec_req_part_start);
     a.req_seg = tab(plan, t.dec_req_seg);
+    a.chain_start = tab(plan, t.dec_chain_start); a.chain = tab(plan, t.dec_chain);
     a.part_o = reinterpret_cast<float*>(static_cast<char*>(workspace) + t.partial_offset);
     a.part_lse = a.part_o + static_cast<size_t>(t.n_dec_parts) * Hq * d;
     a.buf_tokens = plan->buf_tokens; a.n = plan->n;

@@ -112,11 +112,14 @@ __global__ __launch_bounds__(64) void decode_f32_kernel(DecodeArgs a) {
     for (int x = 0; x < kMaxAcc; ++x) st.acc[x] = 0.f;
     const float* kb = static_cast<const float*>(a.kv_buf);
     const float* vb = kb + static_cast<int64_t>(a.Hkv) * a.buf_tokens * a.d;
-    const int32_t* seg = a.req_seg + 4 * i;                 // prefix_off, L_P, suffix_off, L_Q (absolute)
-    for (int s = 0; s < 2; ++s) {
-        const int64_t off = (static_cast<int64_t>(g) * a.buf_tokens + seg[2 * s]) * a.d;
-        attend_segment(st, q_s, s_s, kb + off, vb + off, seg[2 * s + 1] + (s == 1 ? a.grown : 0), a.d, a.d, a.scale);
+    // the request's shared segments, outermost first, then its own suffix (Sec. 3.2, Eq. 5)
+    for (int c = a.chain_start[i]; c < a.chain_start[i + 1]; ++c) {
+        const int64_t off = (static_cast<int64_t>(g) * a.buf_tokens + a.chain[2 * c]) * a.d;
+        attend_segment(st, q_s, s_s, kb + off, vb + off, a.chain[2 * c + 1], a.d, a.d, a.scale);
     }
+    const int32_t* seg = a.req_seg + 4 * i;                 // prefix_off, L_P, suffix_off, L_Q (absolute)
+    const int64_t off = (static_cast<int64_t>(g) * a.buf_tokens + seg[2]) * a.d;
+    attend_segment(st, q_s, s_s, kb + off, vb + off, seg[3] + a.grown, a.d, a.d, a.scale);
     store_row(st, a.out, (static_cast<int64_t>(i) * a.Hq + h) * a.d, a.d, a.out_f32);
 }
 

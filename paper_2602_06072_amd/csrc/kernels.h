@@ -30,6 +30,7 @@ struct DecodeArgs {
     const int32_t* members; const int32_t* member_slot;
     const int32_t* req_part_start;
     const int32_t* req_seg;
+    const int32_t* chain_start; const int32_t* chain;   // per request: (offset, tokens) of its shared segments
     float* part_o; float* part_lse;
     int64_t buf_tokens; int32_t n; int Hq; int Hkv; int d; float scale; int out_f32;
     int32_t grown;                                  // tokens appended to every suffix since the plan was made

@@ -17,7 +17,17 @@ constexpr int kDecodeBlock = PK_KV_BLOCK;   // tokens per buffer tile
 constexpr int kDecodeMaxRows = 32;  // query rows (members x heads-per-KV-head) per work item
 
 struct Member {                     // O_g[i] of Alg. 1 Part 2, offsets relative to the group base
-    int32_t req, prefix_off, lp, suffix_off, lq;
+    int32_t req, prefix_off, lp, suffix_off, lq;   // prefix_off / lp: the innermost shared segment (suffix_off / 0: none)
+    int32_t node = -1;              // index of that segment in Group::nodes
+    int32_t shared = 0;             // tokens of the request that lie in shared segments (its suffix starts there)
+};
+
+struct Node {                       // a shared segment of the group's prefix forest (Sec. 3.2, Eq. 5)
+    int32_t id = 0;                 // the caller's node number (tree plans) or a running number
+    int32_t off = 0, len = 0;       // where it lies in the group buffer
+    int32_t parent = -1;            // index in Group::nodes; parents come first
+    int32_t start = 0;              // logical token position of its first token inside a request
+    std::vector<int32_t> reqs;      // the requests below it, ascending
 };
 
 struct Group {
@@ -25,6 +35,7 @@ struct Group {
     int64_t buf_tokens = 0;         // M(S_g) incl. headroom
     int64_t buf_base = 0;           // token offset of B_g inside the buffer
     std::vector<Member> members;    // layout order
+    std::vector<Node> nodes;        // layout order (a one-level family is one node)
 };
 
 // One array inside the workspace.
@@ -48,7 +59,9 @@ struct DeviceTables {
     TableRef dec_members;           // request ids of the work items' rows
     TableRef dec_member_slot;       // partial slot of each (item, member), -1: the item writes the output
     TableRef dec_req_part_start;    // [n+1] first slot of each request (slots of a request are consecutive)
-    TableRef dec_req_seg;           // [n][4] absolute prefix_off, L_P, suffix_off, L_Q
+    TableRef dec_req_seg;           // [n][4] absolute prefix_off, L_P, suffix_off, L_Q (innermost shared segment)
+    TableRef dec_chain_start;       // [n+1] first entry of each request in dec_chain
+    TableRef dec_chain;             // (absolute offset, tokens) of a request's shared segments, outermost first
     int32_t n_dec_items = 0, n_dec_wide = 0, n_dec_parts = 0, dec_split_tokens = 0;
     int32_t pad_split_tokens = 0, pad_n_splits = 0;   // padded decode comparison: uniform splits
     // prefill (packed and padded schedules share one format)
@@ -78,6 +91,7 @@ struct pk_plan {
     int64_t token_budget = 0;
     int32_t headroom = 0;
     bool decode_only = false;       // every q_len == 1
+    bool tree = false;              // made by pk_pack_plan_tree (nested shared segments)
     std::vector<int32_t> kv_lens, q_lens, prefix_lens;   // prefix_lens: 0 if no family
     std::vector<pk::Group> groups;
     int64_t buf_tokens = 0;         // whole buffer, multiple of PK_KV_BLOCK

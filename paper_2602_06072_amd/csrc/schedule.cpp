@@ -42,16 +42,12 @@ void build_reorg(const pk_plan& plan, Builder& b, DeviceTables& t) {
     struct Seg { int64_t dst0; int32_t ntok, req, src0; };
     std::vector<Seg> segs;
     for (const Group& g : plan.groups) {
-        int32_t last_poff = -1;
-        for (const Member& m : g.members) {
-            if (m.lp > 0 && m.prefix_off != last_poff) {          // prefix once, via its first member
-                segs.push_back({g.buf_base + m.prefix_off, m.lp, m.req, 0});
-                last_poff = m.prefix_off;
-            }
-            if (m.lq > 0) segs.push_back({g.buf_base + m.suffix_off, m.lq, m.req, m.lp});
-        }
+        for (const Node& nd : g.nodes)                            // a shared segment once, via its lowest request
+            segs.push_back({g.buf_base + nd.off, nd.len, nd.reqs[0], nd.start});
+        for (const Member& m : g.members)
+            if (m.lq > 0) segs.push_back({g.buf_base + m.suffix_off, m.lq, m.req, m.shared});
     }
-    // segments are produced in increasing dst0 already (layout order)
+    std::sort(segs.begin(), segs.end(), [](const Seg& x, const Seg& y) { return x.dst0 < y.dst0; });
     std::vector<int32_t> flat;
     flat.reserve(segs.size() * 4);
     for (const Seg& s : segs) {
@@ -103,27 +99,37 @@ void build_decode(const pk_plan& plan, int Hq, int Hkv, Builder& b, DeviceTables
         }
     };
     std::vector<int32_t> req_seg(static_cast<size_t>(plan.n) * 4, 0);
+    std::vector<std::vector<int32_t>> chain_of(static_cast<size_t>(plan.n));
     for (const Group& g : plan.groups) {
-        size_t i = 0;
-        while (i < g.members.size()) {
-            const Member& m = g.members[i];
-            size_t j = i + 1;
-            if (m.lp > 0) {
-                while (j < g.members.size() && g.members[j].lp > 0 &&
-                       g.members[j].prefix_off == m.prefix_off) ++j;
-                std::vector<int32_t> fam;
-                for (size_t k = i; k < j; ++k) fam.push_back(g.members[k].req);
-                add_segment(g.buf_base + m.prefix_off, g.buf_base + m.prefix_off + m.lp, fam, false);
+        // work items in layout order: a shared segment attends for every request below it
+        struct Piece { int32_t off; int32_t node, member; };
+        std::vector<Piece> pieces;
+        for (size_t k = 0; k < g.nodes.size(); ++k) pieces.push_back({g.nodes[k].off, static_cast<int32_t>(k), -1});
+        for (size_t k = 0; k < g.members.size(); ++k) pieces.push_back({g.members[k].suffix_off, -1, static_cast<int32_t>(k)});
+        std::stable_sort(pieces.begin(), pieces.end(), [](const Piece& x, const Piece& y) { return x.off < y.off; });
+        for (const Piece& pc : pieces) {
+            if (pc.node >= 0) {
+                const Node& nd = g.nodes[static_cast<size_t>(pc.node)];
+                add_segment(g.buf_base + nd.off, g.buf_base + nd.off + nd.len, nd.reqs, false);
+                continue;
             }
-            for (size_t k = i; k < j; ++k) {
-                const Member& mm = g.members[k];
-                add_segment(g.buf_base + mm.suffix_off, g.buf_base + mm.suffix_off + mm.lq, {mm.req}, true);
-                int32_t* rs = &req_seg[static_cast<size_t>(mm.req) * 4];
-                rs[0] = static_cast<int32_t>(g.buf_base + mm.prefix_off); rs[1] = mm.lp;
-                rs[2] = static_cast<int32_t>(g.buf_base + mm.suffix_off); rs[3] = mm.lq;
+            const Member& mm = g.members[static_cast<size_t>(pc.member)];
+            add_segment(g.buf_base + mm.suffix_off, g.buf_base + mm.suffix_off + mm.lq, {mm.req}, true);
+            int32_t* rs = &req_seg[static_cast<size_t>(mm.req) * 4];
+            rs[0] = static_cast<int32_t>(g.buf_base + mm.prefix_off); rs[1] = mm.lp;
+            rs[2] = static_cast<int32_t>(g.buf_base + mm.suffix_off); rs[3] = mm.lq;
+            std::vector<int32_t>& ch = chain_of[static_cast<size_t>(mm.req)];
+            for (int32_t k = mm.node; k >= 0; k = g.nodes[static_cast<size_t>(k)].parent) {
+                ch.push_back(g.nodes[static_cast<size_t>(k)].len);            // reversed below: innermost first here
+                ch.push_back(static_cast<int32_t>(g.buf_base + g.nodes[static_cast<size_t>(k)].off));
             }
-            i = j;
+            std::reverse(ch.begin(), ch.end());                   // (offset, tokens) pairs, outermost first
         }
+    }
+    std::vector<int32_t> chain_start(static_cast<size_t>(plan.n) + 1, 0), chain;
+    for (int32_t i = 0; i < plan.n; ++i) {
+        chain.insert(chain.end(), chain_of[static_cast<size_t>(i)].begin(), chain_of[static_cast<size_t>(i)].end());
+        chain_start[static_cast<size_t>(i) + 1] = static_cast<int32_t>(chain.size() / 2);
     }
     // items with more than 16 query rows first (they run the two-column-tile kernel), then
     // the others; inside each class the longest first (stable: deterministic)
@@ -169,6 +175,8 @@ void build_decode(const pk_plan& plan, int Hq, int Hkv, Builder& b, DeviceTables
     t.dec_member_slot = b.add(member_slot);
     t.dec_req_part_start = b.add(start);
     t.dec_req_seg = b.add(req_seg);
+    t.dec_chain_start = b.add(chain_start);
+    t.dec_chain = b.add(chain);
 }
 
 // ---- prefill ---------------------------------------------------------------

@@ -31,25 +31,14 @@ int fail(const char* msg) {
     return PK_EINVAL;
 }
 
-}  // namespace
-
-extern "C" int pk_trie_partition(const int32_t* token_ids, const int32_t* kv_lens, int32_t n,
-                                 int32_t min_prefix, int32_t* prefix_ids, int32_t* prefix_lens,
-                                 int64_t* saved_tokens) {
-    if (n < 0 || min_prefix < 1) return fail("pk_trie_partition: n >= 0 and min_prefix >= 1 required");
-    if (n > 0 && (!token_ids || !kv_lens || !prefix_ids || !prefix_lens))
-        return fail("pk_trie_partition: NULL pointer");
+// Sorts the requests and enumerates the LCP intervals; iv[0] is the whole batch (depth 0), idx the
+// sorted order.  Expects n >= 2 and validated lengths.
+void lcp_intervals(const int32_t* token_ids, const int32_t* kv_lens, int32_t n, int32_t min_prefix,
+                   std::vector<int32_t>& idx, std::vector<Interval>& iv) {
     std::vector<int64_t> start(static_cast<size_t>(n) + 1, 0);
-    for (int32_t i = 0; i < n; ++i) {
-        if (kv_lens[i] <= 0) return fail("pk_trie_partition: kv_len must be positive");
-        start[i + 1] = start[i] + kv_lens[i];
-    }
-    for (int32_t i = 0; i < n; ++i) { prefix_ids[i] = -1; prefix_lens[i] = 0; }
-    if (saved_tokens) *saved_tokens = 0;
-    if (n < 2) return PK_OK;
-
+    for (int32_t i = 0; i < n; ++i) start[i + 1] = start[i] + kv_lens[i];
     auto seq = [&](int32_t i) { return token_ids + start[i]; };
-    std::vector<int32_t> idx(static_cast<size_t>(n));
+    idx.resize(static_cast<size_t>(n));
     std::iota(idx.begin(), idx.end(), 0);
     std::sort(idx.begin(), idx.end(), [&](int32_t a, int32_t b) {
         const int32_t* pa = seq(a); const int32_t* pb = seq(b);
@@ -69,7 +58,6 @@ extern "C" int pk_trie_partition(const int32_t* token_ids, const int32_t* kv_len
         lcp[k] = c;
     }
 
-    std::vector<Interval> iv;
     std::vector<int32_t> stack;
     auto close = [&](int32_t v, int32_t hi) {
         Interval& x = iv[static_cast<size_t>(v)];
@@ -103,6 +91,29 @@ extern "C" int pk_trie_partition(const int32_t* token_ids, const int32_t* kv_len
             iv[static_cast<size_t>(stack.back())].kids.push_back(pending);
         }
     }
+}
+
+int check_lengths(const char* who, const int32_t* kv_lens, int32_t n) {
+    for (int32_t i = 0; i < n; ++i)
+        if (kv_lens[i] <= 0) return fail((std::string(who) + ": kv_len must be positive").c_str());
+    return PK_OK;
+}
+
+}  // namespace
+
+extern "C" int pk_trie_partition(const int32_t* token_ids, const int32_t* kv_lens, int32_t n,
+                                 int32_t min_prefix, int32_t* prefix_ids, int32_t* prefix_lens,
+                                 int64_t* saved_tokens) {
+    if (n < 0 || min_prefix < 1) return fail("pk_trie_partition: n >= 0 and min_prefix >= 1 required");
+    if (n > 0 && (!token_ids || !kv_lens || !prefix_ids || !prefix_lens))
+        return fail("pk_trie_partition: NULL pointer");
+    if (check_lengths("pk_trie_partition", kv_lens, n) != PK_OK) return PK_EINVAL;
+    for (int32_t i = 0; i < n; ++i) { prefix_ids[i] = -1; prefix_lens[i] = 0; }
+    if (saved_tokens) *saved_tokens = 0;
+    if (n < 2) return PK_OK;
+    std::vector<int32_t> idx;
+    std::vector<Interval> iv;
+    lcp_intervals(token_ids, kv_lens, n, min_prefix, idx, iv);
     // the root (depth 0) is closed by lcp[n] = -1
     struct Family { int32_t depth, first; int32_t lo, hi; };
     std::vector<Family> fams;
@@ -127,6 +138,66 @@ extern "C" int pk_trie_partition(const int32_t* token_ids, const int32_t* kv_len
         }
         saved += static_cast<int64_t>(fams[f].depth) * (fams[f].hi - fams[f].lo);
     }
+    if (saved_tokens) *saved_tokens = saved;
+    return PK_OK;
+}
+
+// The whole prefix tree as a forest of shared segments: every LCP interval of at least min_prefix
+// tokens is a node (Eq. 5 applied at every level: a segment of len tokens above m requests saves
+// len * (m - 1)).  Nodes are numbered by (lowest request below, depth), which puts parents first.
+extern "C" int pk_trie_tree(const int32_t* token_ids, const int32_t* kv_lens, int32_t n,
+                            int32_t min_prefix, int32_t* node_parent, int32_t* node_len,
+                            int32_t* n_nodes, int32_t* req_node, int64_t* saved_tokens) {
+    if (n < 0 || min_prefix < 1) return fail("pk_trie_tree: n >= 0 and min_prefix >= 1 required");
+    if (!n_nodes) return fail("pk_trie_tree: n_nodes is NULL");
+    if (n > 0 && (!token_ids || !kv_lens || !node_parent || !node_len || !req_node))
+        return fail("pk_trie_tree: NULL pointer");
+    if (check_lengths("pk_trie_tree", kv_lens, n) != PK_OK) return PK_EINVAL;
+    for (int32_t i = 0; i < n; ++i) req_node[i] = -1;
+    *n_nodes = 0;
+    if (saved_tokens) *saved_tokens = 0;
+    if (n < 2) return PK_OK;
+    std::vector<int32_t> idx;
+    std::vector<Interval> iv;
+    lcp_intervals(token_ids, kv_lens, n, min_prefix, idx, iv);
+
+    struct Seg { int32_t first, depth, parent_depth, lo, hi, parent_iv, number; };
+    std::vector<Seg> segs;
+    std::vector<int32_t> seg_of(iv.size(), -1);
+    // top-down: (interval, nearest ancestor that is a node)
+    std::vector<std::pair<int32_t, int32_t>> walk{{0, -1}};
+    while (!walk.empty()) {
+        const int32_t v = walk.back().first;
+        int32_t anc = walk.back().second;
+        walk.pop_back();
+        const Interval& x = iv[static_cast<size_t>(v)];
+        if (x.depth >= min_prefix) {
+            int32_t first = idx[x.lo];
+            for (int32_t p = x.lo; p <= x.hi; ++p) first = std::min(first, idx[p]);
+            const int32_t pd = anc >= 0 ? iv[static_cast<size_t>(anc)].depth : 0;
+            seg_of[static_cast<size_t>(v)] = static_cast<int32_t>(segs.size());
+            segs.push_back({first, x.depth, pd, x.lo, x.hi, anc, 0});
+            anc = v;
+        }
+        for (int32_t c : x.kids) walk.push_back({c, anc});
+    }
+    std::vector<int32_t> order(segs.size());
+    std::iota(order.begin(), order.end(), 0);
+    std::sort(order.begin(), order.end(), [&](int32_t a, int32_t b) {
+        if (segs[a].first != segs[b].first) return segs[a].first < segs[b].first;
+        return segs[a].depth < segs[b].depth;
+    });
+    for (size_t k = 0; k < order.size(); ++k) segs[static_cast<size_t>(order[k])].number = static_cast<int32_t>(k);
+    int64_t saved = 0;
+    std::vector<int32_t> deepest(static_cast<size_t>(n), 0);
+    for (const Seg& sg : segs) {
+        node_parent[sg.number] = sg.parent_iv >= 0 ? segs[static_cast<size_t>(seg_of[static_cast<size_t>(sg.parent_iv)])].number : -1;
+        node_len[sg.number] = sg.depth - sg.parent_depth;
+        saved += static_cast<int64_t>(sg.depth - sg.parent_depth) * (sg.hi - sg.lo);
+        for (int32_t p = sg.lo; p <= sg.hi; ++p)
+            if (sg.depth > deepest[idx[p]]) { deepest[idx[p]] = sg.depth; req_node[idx[p]] = sg.number; }
+    }
+    *n_nodes = static_cast<int32_t>(segs.size());
     if (saved_tokens) *saved_tokens = saved;
     return PK_OK;
 }

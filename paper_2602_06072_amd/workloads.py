@@ -89,6 +89,11 @@ class PagedDecode:
     q_f32: Optional[torch.Tensor] = None
     k_pages_f32: Optional[torch.Tensor] = None
     v_pages_f32: Optional[torch.Tensor] = None
+    # nested shared prefixes (a forest of segments): parent and length of every node, and the
+    # deepest node above every request (-1: none)
+    node_parent: Optional[np.ndarray] = None
+    node_len: Optional[np.ndarray] = None
+    req_node: Optional[np.ndarray] = None
 
     @property
     def n(self) -> int:
@@ -256,6 +261,42 @@ def make_paged(name, kv_lens, Hq, Hkv, d, token_budget, page_size, seed,
                        None if prefix_ids is None else np.asarray(prefix_ids, np.int32),
                        None if prefix_lens is None else np.asarray(prefix_lens, np.int32),
                        table, q, kp, vp, qf, kpf, vpf)
+
+
+def make_paged_tree(name, suffix_lens, node_parent, node_len, req_node, Hq, Hkv, d, token_budget,
+                    page_size, seed, device="cpu", keep_f32=False) -> PagedDecode:
+    """Decode input whose requests share nested prefixes: a forest of segments (system prompt,
+    then a document below it, ...).  Every request keeps private pages; the requests below a node
+    hold the same K/V values on that node's token range (copied from the lowest request)."""
+    node_parent = np.asarray(node_parent, dtype=np.int32)
+    node_len = np.asarray(node_len, dtype=np.int32)
+    req_node = np.asarray(req_node, dtype=np.int32)
+    depth = np.zeros(len(node_len), dtype=np.int64)
+    for k in range(len(node_len)):
+        depth[k] = node_len[k] + (depth[node_parent[k]] if node_parent[k] >= 0 else 0)
+    kv = np.asarray([int(s) + (int(depth[k]) if k >= 0 else 0) for s, k in zip(suffix_lens, req_node)],
+                    dtype=np.int32)
+    w = make_paged(name, kv, Hq, Hkv, d, token_budget, page_size, seed, device=device, keep_f32=keep_f32)
+    owner = np.full(len(node_len), -1, dtype=np.int64)
+    below = [[] for _ in node_len]
+    for i, k in enumerate(req_node):
+        while k >= 0:
+            below[k].append(i)
+            k = node_parent[k]
+    for k in range(len(node_len)):
+        owner[k] = min(below[k])
+        pos = np.arange(depth[k] - node_len[k], depth[k])
+        src = torch.from_numpy(w.block_table[owner[k], pos // page_size].astype(np.int64)).to(device)
+        slot = torch.from_numpy(pos % page_size).to(device)
+        for i in below[k]:
+            if i == owner[k]:
+                continue
+            dst = torch.from_numpy(w.block_table[i, pos // page_size].astype(np.int64)).to(device)
+            for t in (w.k_pages, w.v_pages, w.k_pages_f32, w.v_pages_f32):
+                if t is not None:
+                    t[dst, slot] = t[src, slot]
+    w.node_parent, w.node_len, w.req_node = node_parent, node_len, req_node
+    return w
 
 
 def config3_lengths(seed=0, n=256) -> np.ndarray:

@@ -237,3 +237,77 @@ def test_trie_partition_error_paths():
     zero = np.array([0], dtype=np.int32)
     assert L.pk_trie_partition(one.ctypes.data, zero.ctypes.data, 1, 1, out.ctypes.data, out.ctypes.data, None) == -1
     assert L.pk_trie_partition(one.ctypes.data, one.ctypes.data, -1, 1, out.ctypes.data, out.ctypes.data, None) == -1
+
+
+# ---- nested shared prefixes: tree plans and the whole prefix tree -----------------------------
+from tests.test_oracle_tree import forests  # noqa: E402  (seeded strategy only, no arithmetic)
+
+
+@settings(max_examples=400, deadline=None)
+@given(forests())
+def test_tree_plan_is_bit_exact_with_oracle(f):
+    kv, parent, length, req_node, C, hr = f
+    words = opl.make_plan_tree(kv, None, parent, length, req_node, C, hr).words()
+    want = np.asarray([w - (1 << 32) if w >= (1 << 31) else w for w in words], dtype=np.int32)
+    got = pk.pack_plan_tree(kv, None, parent, length, req_node, C, hr).words()
+    assert np.array_equal(got, want)
+
+
+def test_tree_plan_of_roots_lays_out_like_uncut_families():
+    kv = [300, 260, 280, 90, 150, 170]
+    pid = [0, 0, 0, -1, 1, 1]
+    plen = [200, 200, 200, 0, 100, 100]
+    flat = pk.pack_plan(kv, [1] * 6, pid, plen, 4096, 2)
+    tree = pk.pack_plan_tree(kv, [1] * 6, [-1, -1], [200, 100], [0, 0, 0, -1, 1, 1], 4096, 2)
+    fw, tw = flat.words(), tree.words()
+    assert fw[1] == 1 and tw[1] == 2
+    assert flat.buf_tokens == tree.buf_tokens and flat.unique_tokens == tree.unique_tokens
+    members_flat = sorted((m[0], m[3], m[4]) for g in flat.groups() for m in g["members"])
+    # version-2 words: walk them by hand
+    w, pos, members_tree = tw.astype(np.int64), 10, []
+    for _ in range(int(w[3])):
+        nn, nm = int(w[pos + 6]), int(w[pos + 7])
+        pos += 8 + 4 * nn
+        members_tree += [(int(w[pos + 4 * j]), int(w[pos + 4 * j + 2]), int(w[pos + 4 * j + 3])) for j in range(nm)]
+        pos += 4 * nm
+    assert pos == len(w) and sorted(members_tree) == members_flat
+
+
+@settings(max_examples=500, deadline=None)
+@given(st.lists(st.lists(st.integers(0, 2), min_size=1, max_size=12), min_size=0, max_size=14), st.integers(1, 4))
+def test_trie_tree_equals_oracle(seqs, min_prefix):
+    from oracle import trie
+    par, ln, rn, saved = trie.trie_tree(seqs, min_prefix)
+    gpar, gln, grn, gsaved = pk.trie_tree(seqs, min_prefix)
+    assert list(gpar) == par and list(gln) == ln and list(grn) == rn and gsaved == saved
+
+
+def test_trie_tree_feeds_the_tree_planner():
+    rng = np.random.default_rng(5)
+    system = rng.integers(0, 1000, 300).tolist()
+    docs = [rng.integers(0, 1000, 200).tolist() for _ in range(3)]
+    seqs = []
+    for i in range(12):
+        seqs.append(system + docs[i % 3] + rng.integers(1000, 2000, int(rng.integers(20, 90))).tolist())
+    seqs.append(rng.integers(2000, 3000, 77).tolist())
+    par, ln, rn, saved = pk.trie_tree(seqs, 16)
+    assert list(par) == [-1, 0, 0, 0] and list(ln) == [300, 200, 200, 200]
+    assert saved == 300 * 11 + 3 * 200 * 3
+    kv = [len(s) for s in seqs]
+    plan = pk.pack_plan_tree(kv, [1] * len(seqs), par, ln, rn, 8192, 4)
+    assert plan.unique_tokens == sum(kv) - saved
+
+
+def test_tree_plan_error_paths():
+    bad = [
+        dict(node_parent=[0], node_len=[4], req_node=[0]),           # parent not below its own number
+        dict(node_parent=[-1], node_len=[0], req_node=[0]),          # empty segment
+        dict(node_parent=[-1], node_len=[4], req_node=[1]),          # node out of range
+        dict(node_parent=[-1], node_len=[40], req_node=[0]),         # request shorter than its prefix
+        dict(node_parent=[-1, -1], node_len=[4, 4], req_node=[0]),   # a node without requests
+    ]
+    for kw in bad:
+        with pytest.raises(pk.PackInferError):
+            pk.pack_plan_tree([10], None, token_budget=64, headroom=0, **kw)
+    with pytest.raises(pk.PackInferError):
+        pk.trie_tree([[1, 2]], 0)
