@@ -80,7 +80,7 @@ void lcp_intervals(const int32_t* token_ids, const int32_t* kv_lens, int32_t n, 
             lb = iv[static_cast<size_t>(v)].lo;
             pending = v;
         }
-        if (stack.empty()) break;                   // k == n: the root itself was closed
+        if (stack.empty()) break;                   // k == n: lcp[n] = -1 closed the root (depth 0) itself
         if (lcp[k] > iv[static_cast<size_t>(stack.back())].depth) {
             Interval x;
             x.depth = lcp[k]; x.lo = lb;
@@ -114,7 +114,6 @@ extern "C" int pk_trie_partition(const int32_t* token_ids, const int32_t* kv_len
     std::vector<int32_t> idx;
     std::vector<Interval> iv;
     lcp_intervals(token_ids, kv_lens, n, min_prefix, idx, iv);
-    // the root (depth 0) is closed by lcp[n] = -1
     struct Family { int32_t depth, first; int32_t lo, hi; };
     std::vector<Family> fams;
     std::vector<int32_t> walk{0};

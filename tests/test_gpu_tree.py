@@ -149,3 +149,35 @@ def test_tree_multi_step_decode_with_headroom(use_f32):
         want, _ = oa.attention_ragged(q.float().numpy(), np.concatenate(K), np.concatenate(V),
                                       [1] * w.n, lens, w.scale)
         H.assert_close(out.cpu().numpy(), want, 1 if use_f32 else 0, f"tree step {t}")
+
+
+def test_from_token_ids_to_decode():
+    # token ids -> pk_trie_tree -> pk_pack_plan_tree -> re-layout -> decode, against the oracle
+    rng = np.random.default_rng(7)
+    fresh = iter(range(10, 10 ** 6))                 # every drawn token id is new: no accidental sharing
+
+    def toks(k):
+        return [next(fresh) for _ in range(k)]
+
+    system, docs = toks(90), [toks(60), toks(41)]
+    turns = [toks(25), toks(33)]
+    seqs = []
+    for i in range(12):
+        s = system + docs[i % 2]
+        if i % 2 == 0 and i % 4 == 0:
+            s = s + turns[(i // 4) % 2]
+        seqs.append(s + toks(int(rng.integers(1, 120))))
+    seqs.append(toks(200))                           # no shared prefix at all
+    seqs.append(system + docs[0])                    # ends exactly where a shared segment ends
+    par, ln, rn, saved = pk.trie_tree(seqs, 8)
+    kv = np.asarray([len(s) for s in seqs], dtype=np.int32)
+    depth = np.zeros(len(ln), dtype=np.int64)
+    for k in range(len(ln)):
+        depth[k] = ln[k] + (depth[par[k]] if par[k] >= 0 else 0)
+    suffix = [int(kv[i] - (depth[rn[i]] if rn[i] >= 0 else 0)) for i in range(len(seqs))]
+    assert min(suffix) == 0 and len(ln) >= 4 and saved > 0
+    w = to_dev(wl.make_paged_tree("from_tokens", suffix, par, ln, rn, 8, 2, 128, 4096, 16, 31, keep_f32=False))
+    assert np.array_equal(w.kv_lens, kv)
+    got, plan, _, _ = run(w, False, 4096)
+    assert plan.unique_tokens == int(kv.sum()) - saved
+    H.assert_close(got, H.oracle_paged_decode(w, False), 0, "decode from token ids")
