@@ -270,6 +270,51 @@ def capacity_sweep(wl, pk, seed, dev):
     return rows
 
 
+def prefix_tree_bench(wl, pk, seed, dev):
+    """Nested shared prefixes (Sec. 3.2 "Prefix-Aware Grouping and Reuse", Eq. 5): a batch of 128
+    decode requests of an 8B-shaped model that all share a system prompt of 2048 tokens and, in
+    16 families of 8, a document of 1024 tokens below it, with private tails of 32..512 tokens.
+    Re-layout and one decode step with (a) no prefix information, (b) the one-level TriePartition,
+    (c) the whole prefix tree.  Token ids are synthetic; the planner sees only them."""
+    import time
+    import torch
+    rng = np.random.default_rng(seed + 303)
+    fresh = iter(range(1, 1 << 30))
+    system = [next(fresh) for _ in range(2048)]
+    docs = [[next(fresh) for _ in range(1024)] for _ in range(16)]
+    tails = rng.integers(32, 513, size=128)
+    seqs = [system + docs[i // 8] + [next(fresh) for _ in range(int(tails[i]))] for i in range(128)]
+    kv = np.asarray([len(s) for s in seqs], dtype=np.int32)
+    t0 = time.perf_counter(); ids, plens, saved1 = pk.trie_partition(seqs, 16); t1 = time.perf_counter()
+    par, ln, rn, saved2 = pk.trie_tree(seqs, 16); t2 = time.perf_counter()
+    depth = np.zeros(len(ln), dtype=np.int64)
+    for k in range(len(ln)):
+        depth[k] = ln[k] + (depth[par[k]] if par[k] >= 0 else 0)
+    suffix = [int(kv[i] - (depth[rn[i]] if rn[i] >= 0 else 0)) for i in range(len(seqs))]
+    w = wl.make_paged_tree("prefix_tree", suffix, par, ln, rn, 32, 8, 128, 8192, 16, seed, device=dev)
+    assert np.array_equal(w.kv_lens, kv)
+    ones = np.ones_like(kv)
+    bt = torch.from_numpy(w.block_table).to(dev)
+    out = torch.empty(w.q.shape, dtype=torch.bfloat16, device=dev)
+    plans = {"no_prefix_information": pk.pack_plan(kv, ones, None, None, 8192),
+             "one_level_trie_partition": pk.pack_plan(kv, ones, ids, plens, 8192),
+             "prefix_tree": pk.pack_plan_tree(kv, ones, par, ln, rn, 8192)}
+    res = {"requests": len(seqs), "kv_tokens_naive": int(kv.sum()),
+           "trie_partition_host_ms": (t1 - t0) * 1e3, "trie_tree_host_ms": (t2 - t1) * 1e3,
+           "saved_tokens_one_level": int(saved1), "saved_tokens_tree": int(saved2), "tree_nodes": int(len(ln))}
+    for name, plan in plans.items():
+        ws = pk.new_workspace(plan, w.Hq, w.Hkv, w.d, pk.PK_BF16)
+        pk.plan_bind(plan, w.Hq, w.Hkv, w.d, pk.PK_BF16, ws)
+        buf = pk.new_kv_buf(plan, w.Hkv, w.d, pk.PK_BF16)
+        r_ms, _ = _time_launches(lambda: pk.kv_reorganize(plan, w.k_pages, w.v_pages, bt, buf, ws), 20)
+        d_ms, _ = _time_launches(lambda: pk.packed_decode_attn(plan, w.q, buf, out, w.scale, w.Hkv, ws), 50)
+        kv_bytes = plan.unique_tokens * w.Hkv * w.d * 2 * 2
+        res[name] = {"groups": plan.num_groups, "unique_tokens": plan.unique_tokens, "kv_bytes_unique": kv_bytes,
+                     "reorg_ms": r_ms, "decode_ms": d_ms, "decode_gbs_unique": kv_bytes / (d_ms * 1e-3) / 1e9}
+        del buf, ws
+    return res
+
+
 def motivation_replay(wl, pk, seed, dev):
     """Analogue of the paper's motivation experiment (Sec. 2.2, heterogeneous against homogeneous
     batches with the same number of requests and the same total tokens), plus a mix in which more
@@ -361,6 +406,8 @@ def main():
                     help="also run a plain elementwise kernel over 1 GiB 5 times (reference for HBM byte counters)")
     ap.add_argument("--motivation", action="store_true",
                     help="instead of the benchmark line: homogeneous / heterogeneous / skewed batches of equal size (one JSON line)")
+    ap.add_argument("--prefix-tree", action="store_true",
+                    help="instead of the benchmark line: decode with no / one-level / nested shared prefixes (one JSON line)")
     ap.add_argument("--capacity-sweep", action="store_true",
                     help="instead of the benchmark line: profile the group capacity C over a range (one JSON line)")
     args = ap.parse_args()
@@ -381,6 +428,9 @@ def main():
 
     if args.motivation:
         print(json.dumps({"motivation_replay": motivation_replay(wl, pk, args.seed, dev), "seed": args.seed}))
+        return
+    if args.prefix_tree:
+        print(json.dumps({"prefix_tree": prefix_tree_bench(wl, pk, args.seed, dev), "seed": args.seed}))
         return
     if args.capacity_sweep:
         print(json.dumps({"capacity_sweep": capacity_sweep(wl, pk, args.seed, dev), "seed": args.seed,
