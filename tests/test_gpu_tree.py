@@ -181,3 +181,22 @@ def test_from_token_ids_to_decode():
     got, plan, _, _ = run(w, False, 4096)
     assert plan.unique_tokens == int(kv.sum()) - saved
     H.assert_close(got, H.oracle_paged_decode(w, False), 0, "decode from token ids")
+
+
+@pytest.mark.parametrize("use_f32", [True, False])
+def test_prefill_on_a_tree_plan(use_f32):
+    # chunked prefill with a plan whose groups come from a prefix forest: the query tiles follow the
+    # tree layout's member order; attention itself reads the caller's ragged K/V
+    w = to_dev(wl.small_ragged(seed=41, n=9, lo=1, hi=260, Hq=4, Hkv=2, d=128, token_budget=700, ctx_hi=300))
+    kv = w.kv_lens
+    node_parent, node_len = [-1, 0, -1], [20, 15, 11]
+    req_node = [(1, 0, 2)[i % 3] for i in range(len(kv))]
+    assert kv.min() >= 35                           # every request is longer than the segments above it
+    plan = pk.pack_plan_tree(kv, w.q_lens, node_parent, node_len, req_node, w.token_budget, 0)
+    q, k, v = (w.q_f32, w.k_f32, w.v_f32) if use_f32 else (w.q, w.k, w.v)
+    code = pk.PK_F32 if use_f32 else pk.PK_BF16
+    ws = pk.new_workspace(plan, w.Hq, w.Hkv, w.d, code)
+    out = torch.full(q.shape, float("nan"), dtype=torch.float32, device=DEV)
+    pk.packed_prefill_attn(plan, q, k, v, out, w.scale, ws)
+    torch.cuda.synchronize()
+    H.assert_close(out.cpu().numpy(), H.oracle_ragged(w, use_f32), 1 if use_f32 else 0, "prefill on a tree plan")
