@@ -71,9 +71,11 @@ void build_reorg(const pk_plan& plan, Builder& b, DeviceTables& t) {
 void build_decode(const pk_plan& plan, int Hq, int Hkv, Builder& b, DeviceTables& t) {
     const int r = Hq / Hkv;
     const int max_members = std::max(1, kDecodeMaxRows / r);
-    // split length: enough work items to fill the chip, long enough to amortise the partials
-    int64_t split = (plan.unique_tokens * Hkv / 4096 + kDecodeBlock - 1) / kDecodeBlock * kDecodeBlock;
-    split = std::min<int64_t>(std::max<int64_t>(split, 256), 2048);
+    // split length: about 1500 waves (work items x KV heads) keep enough loads in flight to fill
+    // the memory system (each has 64 KiB outstanding); beyond that, longer items mean fewer
+    // partial results to write and merge
+    int64_t split = (plan.unique_tokens * Hkv / 1536 + kDecodeBlock - 1) / kDecodeBlock * kDecodeBlock;
+    split = std::min<int64_t>(std::max<int64_t>(split, 128), 2048);
     split = env_int("PK_DECODE_SPLIT", static_cast<int>(split));
     split = (split + kDecodeBlock - 1) / kDecodeBlock * kDecodeBlock;
     t.dec_split_tokens = static_cast<int32_t>(split);
