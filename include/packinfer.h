@@ -24,7 +24,13 @@
  *     Small integer tables are copied host->device on that stream when a
  *     plan is first used with a workspace (see pk_plan_bind).
  *   - All tensors are in CALLER REQUEST ORDER; the permutation into groups
- *     is internal.
+ *     is internal.  Every tensor pointer (q, k, v, out, pages, kv_buf, new
+ *     rows) must be 16-byte aligned (PK_EINVAL otherwise).
+ *   - A plan carries its device tables and the workspace it is bound to:
+ *     calls on ONE plan must not run concurrently from several host threads,
+ *     and launches that share a workspace must be ordered on the stream(s)
+ *     by the caller (decode keeps partial results there).  Different plans
+ *     may be used from different threads.
  *   - Return value: PK_OK (0) or a negative PK_E* code; the message is
  *     available from pk_last_error() (thread-local).  Arguments are checked
  *     before anything is launched.  Nothing throws or aborts.

@@ -2,6 +2,7 @@
 #include <hip/hip_runtime_api.h>
 
 #include <cstring>
+#include <initializer_list>
 #include <mutex>
 #include <string>
 #include <vector>
@@ -22,6 +23,13 @@ int hip_fail(const char* where, int err) {
     return fail(PK_EHIP, std::string(where) + ": " + hipGetErrorString(static_cast<hipError_t>(err)));
 }
 
+// the kernels move 16 bytes per lane: every tensor pointer must be 16-byte aligned
+bool aligned16(std::initializer_list<const void*> ptrs) {
+    for (const void* p : ptrs)
+        if (reinterpret_cast<uintptr_t>(p) % 16 != 0) return false;
+    return true;
+}
+
 bool shape_ok(int Hq, int Hkv, int d, int dtype, std::string& why) {
     if (Hq <= 0 || Hkv <= 0 || d <= 0 || Hq % Hkv != 0) { why = "need Hq, Hkv, d > 0 and Hq % Hkv == 0"; return false; }
     if (dtype != PK_BF16 && dtype != PK_F32) { why = "dtype must be PK_BF16 or PK_F32"; return false; }
@@ -37,6 +45,7 @@ struct Staging {
     size_t cap = 0;
     hipEvent_t done = nullptr;
     bool used = false;                              // an event has been recorded for it
+    bool busy = false;                              // handed out and not yet released by copy_tables
 };
 std::mutex g_staging_mutex;
 std::vector<Staging> g_staging;
@@ -44,7 +53,7 @@ std::vector<Staging> g_staging;
 Staging* staging_acquire(size_t bytes) {
     std::lock_guard<std::mutex> lock(g_staging_mutex);
     for (Staging& s : g_staging)
-        if (s.cap >= bytes && (!s.used || hipEventQuery(s.done) == hipSuccess)) return &s;
+        if (!s.busy && s.cap >= bytes && (!s.used || hipEventQuery(s.done) == hipSuccess)) { s.busy = true; return &s; }
     if (g_staging.size() >= 64) return nullptr;     // fall back to a pageable copy
     Staging s;
     s.cap = (bytes + (1u << 20) - 1) >> 20 << 20;
@@ -52,9 +61,17 @@ Staging* staging_acquire(size_t bytes) {
     if (hipEventCreateWithFlags(&s.done, hipEventDisableTiming) != hipSuccess) {
         (void)hipGetLastError(); (void)hipHostFree(s.ptr); return nullptr;
     }
+    s.busy = true;
     g_staging.reserve(64);                          // pointers into the vector stay valid
     g_staging.push_back(s);
     return &g_staging.back();
+}
+
+// recorded: the event behind the copy has been recorded (otherwise the buffer is free at once)
+void staging_release(Staging* s, bool recorded) {
+    std::lock_guard<std::mutex> lock(g_staging_mutex);
+    s->used = recorded;
+    s->busy = false;
 }
 
 int copy_tables(void* dst, const void* src, size_t bytes, void* stream) {
@@ -63,9 +80,15 @@ int copy_tables(void* dst, const void* src, size_t bytes, void* stream) {
     if (!s) return static_cast<int>(hipMemcpyAsync(dst, src, bytes, hipMemcpyHostToDevice, st));
     std::memcpy(s->ptr, src, bytes);
     hipError_t e = hipMemcpyAsync(dst, s->ptr, bytes, hipMemcpyHostToDevice, st);
-    if (e != hipSuccess) return static_cast<int>(e);
+    if (e != hipSuccess) {
+        // the copy may or may not have been queued: keep the buffer out of circulation until the stream drains
+        (void)hipStreamSynchronize(st);
+        staging_release(s, false);
+        return static_cast<int>(e);
+    }
     e = hipEventRecord(s->done, st);
-    s->used = true;
+    if (e != hipSuccess) (void)hipStreamSynchronize(st);    // no event to wait for: drain instead
+    staging_release(s, e == hipSuccess);
     return static_cast<int>(e);
 }
 
@@ -146,6 +169,7 @@ extern "C" int pk_kv_reorganize(pk_plan* plan, const void* k_pages, const void* 
     if (!plan) return fail(PK_EINVAL, "pk_kv_reorganize: plan is NULL");
     if (plan->n == 0) return PK_OK;
     if (!k_pages || !v_pages || !block_table || !kv_buf) return fail(PK_EINVAL, "pk_kv_reorganize: NULL pointer");
+    if (!aligned16({k_pages, v_pages, kv_buf})) return fail(PK_EINVAL, "pk_kv_reorganize: tensors must be 16-byte aligned");
     if (page_size <= 0 || num_blocks <= 0) return fail(PK_EINVAL, "pk_kv_reorganize: page_size and num_blocks must be positive");
     int Hq = plan->tables.Hkv == Hkv && plan->tables.d == d && plan->tables.dtype == dtype ? plan->tables.Hq : Hkv;
     if (!shape_ok(Hq, Hkv, d, dtype, why)) return fail(PK_EINVAL, "pk_kv_reorganize: " + why);
@@ -174,6 +198,7 @@ static int prefill_common(pk_plan* plan, const void* q, const void* k, const voi
     if (!plan) return fail(PK_EINVAL, std::string(who) + ": plan is NULL");
     if (plan->n == 0) return PK_OK;
     if (!q || !k || !v || !out) return fail(PK_EINVAL, std::string(who) + ": NULL pointer");
+    if (!aligned16({q, k, v, out})) return fail(PK_EINVAL, std::string(who) + ": tensors must be 16-byte aligned");
     if (!shape_ok(Hq, Hkv, d, dtype, why)) return fail(PK_EINVAL, std::string(who) + ": " + why);
     if (out_dtype != PK_BF16 && out_dtype != PK_F32) return fail(PK_EINVAL, std::string(who) + ": bad out_dtype");
     if (dtype == PK_BF16 && d != 64 && d != 128) return fail(PK_EUNSUPPORTED, std::string(who) + ": bf16 path needs d in {64,128}");
@@ -229,6 +254,7 @@ int decode_common(const char* who, pk_plan* plan, const void* q, const void* kv_
     if (plan->n == 0) return PK_OK;
     if (!plan->decode_only) return fail(PK_EINVAL, w + ": the plan must have q_len == 1 for every request");
     if (!q || !kv_buf || !out) return fail(PK_EINVAL, w + ": NULL pointer");
+    if (!aligned16({q, kv_buf, out})) return fail(PK_EINVAL, w + ": tensors must be 16-byte aligned");
     if (grown < 0 || grown > plan->headroom)
         return fail(PK_EINVAL, w + ": grown must be in [0, headroom] (regroup when the headroom is used up)");
     if (!shape_ok(Hq, Hkv, d, dtype, why)) return fail(PK_EINVAL, w + ": " + why);
@@ -281,6 +307,7 @@ extern "C" int pk_kv_append(pk_plan* plan, const void* k_new, const void* v_new,
     if (plan->n == 0) return PK_OK;
     if (!plan->decode_only) return fail(PK_EINVAL, "pk_kv_append: the plan must have q_len == 1 for every request");
     if (!k_new || !v_new || !kv_buf) return fail(PK_EINVAL, "pk_kv_append: NULL pointer");
+    if (!aligned16({k_new, v_new, kv_buf})) return fail(PK_EINVAL, "pk_kv_append: tensors must be 16-byte aligned");
     if (step < 0 || step >= plan->headroom)
         return fail(PK_EINVAL, "pk_kv_append: step must be in [0, headroom): no slot left, regroup");
     int Hq = plan->tables.Hkv == Hkv && plan->tables.d == d && plan->tables.dtype == dtype ? plan->tables.Hq : Hkv;
@@ -334,6 +361,7 @@ extern "C" int pk_padded_decode_attn(pk_plan* plan, const void* q,
     if (plan->n == 0) return PK_OK;
     if (!plan->decode_only) return fail(PK_EINVAL, "pk_padded_decode_attn: the plan must have q_len == 1 for every request");
     if (!q || !k_pages || !v_pages || !block_table || !out) return fail(PK_EINVAL, "pk_padded_decode_attn: NULL pointer");
+    if (!aligned16({q, k_pages, v_pages, out})) return fail(PK_EINVAL, "pk_padded_decode_attn: tensors must be 16-byte aligned");
     if (page_size <= 0 || num_blocks <= 0) return fail(PK_EINVAL, "pk_padded_decode_attn: page_size and num_blocks must be positive");
     if (!shape_ok(Hq, Hkv, d, dtype, why)) return fail(PK_EINVAL, "pk_padded_decode_attn: " + why);
     if (out_dtype != PK_BF16 && out_dtype != PK_F32) return fail(PK_EINVAL, "pk_padded_decode_attn: bad out_dtype");

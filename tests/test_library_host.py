@@ -311,3 +311,13 @@ def test_tree_plan_error_paths():
             pk.pack_plan_tree([10], None, token_budget=64, headroom=0, **kw)
     with pytest.raises(pk.PackInferError):
         pk.trie_tree([[1, 2]], 0)
+
+
+def test_misaligned_tensor_pointers_are_rejected_before_any_launch():
+    plan = pk.pack_plan([40, 50], None, None, None, 128, 0)
+    L = pk.lib()
+    bad = ctypes.c_void_p(0x1008)                  # not 16-byte aligned; never dereferenced
+    ok = ctypes.c_void_p(0x1000)
+    rc = L.pk_packed_prefill_attn(plan.handle, bad, ok, ok, ok, ctypes.c_float(1.0), 4, 2, 128, pk.PK_BF16, pk.PK_F32,
+                                  ok, 1 << 20, None)
+    assert rc == -1 and b"16-byte" in L.pk_last_error()
