@@ -6,6 +6,8 @@
 #include <map>
 #include <new>
 #include <numeric>
+#include <queue>
+#include <utility>
 
 #include "plan.h"
 
@@ -62,18 +64,23 @@ int finish_plan(pk_plan* plan, std::vector<Item>& items, const int32_t* kv_lens,
         if (items[a].length != items[b].length) return items[a].length > items[b].length;
         return items[a].first < items[b].first;
     });
+    // arg min over the group loads (lowest index on ties) through a heap of (load, index): only the
+    // chosen group's load changes, so a request costs O(log G) instead of a scan of all groups
+    using Slot = std::pair<int64_t, size_t>;
+    std::priority_queue<Slot, std::vector<Slot>, std::greater<Slot>> least;
+    for (size_t g = 0; g < loads.size(); ++g) least.push({0, g});
     for (int32_t idx : order) {
         const Item& it = items[idx];
-        size_t g = 0;
-        bool have = !loads.empty();
-        for (size_t j = 1; j < loads.size(); ++j)
-            if (loads[j] < loads[g]) g = j;                       // lowest index on ties
-        if (have && loads[g] + it.length <= C) {
+        if (!least.empty() && least.top().first + it.length <= C) {
+            const size_t g = least.top().second;
+            least.pop();
             loads[g] += it.length;
             assigned[g].push_back(idx);
+            least.push({loads[g], g});
         } else {                                                  // else-branch: open a new group
             loads.push_back(it.length);
             assigned.push_back({idx});
+            least.push({it.length, loads.size() - 1});
         }
     }
 
