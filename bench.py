@@ -456,6 +456,7 @@ def main():
         w4 = wl.config4(args.seed, device=dev)
         extra["decode_cfg4_shared_prefix"] = bench_decode(w4, 20)
         del w4
+        extra["decode_nested_prefixes"] = prefix_tree_bench(wl, pk, args.seed, dev)
         torch.cuda.empty_cache()
         w5 = wl.config5(args.seed, device=dev)
         extra["prefill_cfg5_70b_chunks"] = bench_prefill(w5.prefill, 5, 2)

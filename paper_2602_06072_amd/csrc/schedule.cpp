@@ -90,13 +90,18 @@ void build_decode(const pk_plan& plan, int Hq, int Hkv, Builder& b, DeviceTables
             if (suffix && plan.headroom > 0) { items.push_back({a, a, reqs}); items.back().grows = true; }
             return;
         }
+        // the fewest pieces of at most `split` tokens, all of (nearly) the same length: a full-length
+        // piece next to a short remainder would set the pace of the launch for little work
         const int64_t a_blk = a / kDecodeBlock * kDecodeBlock;
+        const int64_t blocks = (e - a_blk + kDecodeBlock - 1) / kDecodeBlock;
+        const int64_t pieces = (blocks * kDecodeBlock + split - 1) / split;
+        const int64_t piece = (blocks + pieces - 1) / pieces * kDecodeBlock;
         for (size_t m0 = 0; m0 < reqs.size(); m0 += max_members) {
             std::vector<int32_t> chunk(reqs.begin() + m0,
                                        reqs.begin() + std::min(reqs.size(), m0 + max_members));
-            for (int64_t p0 = a_blk; p0 < e; p0 += split) {
-                items.push_back({std::max(a, p0), std::min(e, p0 + split), chunk});
-                items.back().grows = suffix && p0 + split >= e;
+            for (int64_t p0 = a_blk; p0 < e; p0 += piece) {
+                items.push_back({std::max(a, p0), std::min(e, p0 + piece), chunk});
+                items.back().grows = suffix && p0 + piece >= e;
             }
         }
     };
