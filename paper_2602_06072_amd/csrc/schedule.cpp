@@ -76,6 +76,28 @@ void build_decode(const pk_plan& plan, int Hq, int Hkv, Builder& b, DeviceTables
     // partial results to write and merge
     int64_t split = (plan.unique_tokens * Hkv / 1536 + kDecodeBlock - 1) / kDecodeBlock * kDecodeBlock;
     split = std::min<int64_t>(std::max<int64_t>(split, 128), 2048);
+    {
+        // All waves of the launch should be resident at once (a second, partly filled round of
+        // waves is a tail as long as a whole item): 16 waves per CU fit, 8 of the kernel that
+        // also handles 32-row items.  Short suffixes cost an item each whatever the split, so the
+        // items are counted for the candidate and the split is raised until they fit.
+        bool wide = false;
+        for (const Group& g : plan.groups)
+            for (const Node& nd : g.nodes) wide = wide || static_cast<int>(std::min<size_t>(nd.reqs.size(), max_members)) * r > 16;
+        const int64_t capacity = (wide ? 8 : 16) * 256 * 9 / 10;
+        auto pieces_of = [&](int64_t len, int64_t sp) { return len <= 0 ? int64_t{0} : ((len + kDecodeBlock - 1) / kDecodeBlock * kDecodeBlock + sp - 1) / sp; };
+        auto count_items = [&](int64_t sp) {
+            int64_t c = 0;
+            for (const Group& g : plan.groups) {
+                for (const Node& nd : g.nodes)
+                    c += pieces_of(nd.len, sp) * static_cast<int64_t>((nd.reqs.size() + max_members - 1) / max_members);
+                for (const Member& m : g.members) c += std::max<int64_t>(pieces_of(m.lq, sp), plan.headroom > 0 ? 1 : 0);
+            }
+            return c;
+        };
+        while (split < 2048 && count_items(split) * Hkv > capacity)
+            split = std::min<int64_t>(2048, (split * 5 / 4 + kDecodeBlock - 1) / kDecodeBlock * kDecodeBlock);
+    }
     split = env_int("PK_DECODE_SPLIT", static_cast<int>(split));
     split = (split + kDecodeBlock - 1) / kDecodeBlock * kDecodeBlock;
     t.dec_split_tokens = static_cast<int32_t>(split);
