@@ -164,19 +164,33 @@ class Plan:
         return out
 
     def groups(self):
-        """Parsed view: list of dicts(load, buf_tokens, buf_base, members[(req, poff, lp, soff, lq)])."""
-        w = self.words().astype(np.int64) & 0xFFFFFFFF
-        G = int(w[3])
+        """Parsed view of the canonical words: a list of dicts(load, buf_tokens, buf_base, members, nodes).
+        Plans of pack_plan: members = (req, prefix_off, L_P, suffix_off, L_Q), nodes = [].
+        Plans of pack_plan_tree: nodes = (node id, off, len, parent index or -1),
+        members = (req, node index or -1, suffix_off, suffix tokens)."""
+        raw = self.words()
+        w = raw.astype(np.int64) & 0xFFFFFFFF
+        version, G = int(w[1]), int(w[3])
         pos, out = 10, []
         for _ in range(G):
             load = int(w[pos] | (w[pos + 1] << 32))
             bt = int(w[pos + 2] | (w[pos + 3] << 32))
             bb = int(w[pos + 4] | (w[pos + 5] << 32))
-            nm = int(w[pos + 6])
-            pos += 7
-            mem = [tuple(int(x) for x in w[pos + 5 * j: pos + 5 * j + 5]) for j in range(nm)]
-            pos += 5 * nm
-            out.append(dict(load=load, buf_tokens=bt, buf_base=bb, members=mem))
+            pos += 6
+            nodes = []
+            if version == 2:
+                nn, nm = int(w[pos]), int(w[pos + 1])
+                pos += 2
+                nodes = [tuple(int(x) for x in raw[pos + 4 * j: pos + 4 * j + 4]) for j in range(nn)]
+                pos += 4 * nn
+                mem = [tuple(int(x) for x in raw[pos + 4 * j: pos + 4 * j + 4]) for j in range(nm)]
+                pos += 4 * nm
+            else:
+                nm = int(w[pos])
+                pos += 1
+                mem = [tuple(int(x) for x in raw[pos + 5 * j: pos + 5 * j + 5]) for j in range(nm)]
+                pos += 5 * nm
+            out.append(dict(load=load, buf_tokens=bt, buf_base=bb, members=mem, nodes=nodes))
         return out
 
     def stat(self, what: int) -> int:

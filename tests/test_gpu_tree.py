@@ -22,22 +22,8 @@ def to_dev(w):
 
 
 def tree_groups(plan):
-    """Version-2 plan words -> list of dict(buf_base, buf_tokens, nodes, members)."""
-    w = plan.words().astype(np.int64) & 0xFFFFFFFF
-    assert int(w[1]) == 2
-    pos, out = 10, []
-    for _ in range(int(w[3])):
-        bt = int(w[pos + 2] | (w[pos + 3] << 32))
-        bb = int(w[pos + 4] | (w[pos + 5] << 32))
-        nn, nm = int(w[pos + 6]), int(w[pos + 7])
-        pos += 8
-        sg = lambda x: int(x) - (1 << 32) if int(x) >= (1 << 31) else int(x)
-        nodes = [tuple(sg(x) for x in w[pos + 4 * j: pos + 4 * j + 4]) for j in range(nn)]
-        pos += 4 * nn
-        members = [tuple(sg(x) for x in w[pos + 4 * j: pos + 4 * j + 4]) for j in range(nm)]
-        pos += 4 * nm
-        out.append(dict(buf_base=bb, buf_tokens=bt, nodes=nodes, members=members))
-    return out
+    assert int(plan.words()[1]) == 2
+    return plan.groups()
 
 
 # system prompt -> two documents -> (under document 0) two conversation branches; one request

@@ -321,3 +321,14 @@ def test_misaligned_tensor_pointers_are_rejected_before_any_launch():
     rc = L.pk_packed_prefill_attn(plan.handle, bad, ok, ok, ok, ctypes.c_float(1.0), 4, 2, 128, pk.PK_BF16, pk.PK_F32,
                                   ok, 1 << 20, None)
     assert rc == -1 and b"16-byte" in L.pk_last_error()
+
+
+def test_parsed_groups_of_a_tree_plan():
+    plan = pk.pack_plan_tree([100, 110, 120, 130, 40], None, [-1, 0, 0], [50, 30, 20], [1, 1, 2, 0, -1], 4096, 0)
+    gs = plan.groups()
+    nodes = [nd for g in gs for nd in g["nodes"]]
+    members = [m for g in gs for m in g["members"]]
+    assert sorted(nd[0] for nd in nodes) == [0, 1, 2] and sorted(m[0] for m in members) == [0, 1, 2, 3, 4]
+    assert sum(nd[2] for nd in nodes) + sum(m[3] for m in members) == plan.unique_tokens
+    flat = pk.pack_plan([10, 20], None, None, None, 64, 0).groups()
+    assert flat[0]["nodes"] == [] and len(flat[0]["members"][0]) == 5
