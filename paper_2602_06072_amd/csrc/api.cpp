@@ -215,7 +215,7 @@ static int prefill_common(pk_plan* plan, const void* q, const void* k, const voi
     PrefillArgs a{};
     a.q = q; a.k = k; a.v = v; a.out = out;
     a.tiles = tab(plan, s.tiles, base); a.n_tiles = s.n_tiles;
-    a.row_q = tab(plan, s.row_q, base); a.row_lo = tab(plan, s.row_lo, base); a.row_hi = tab(plan, s.row_hi, base);
+    a.run_first = tab(plan, s.run_first, base); a.runs = tab(plan, s.runs, base);
     a.kvtiles = tab(plan, s.kvtiles, base);
     a.q_start = tab(plan, t.q_start); a.kv_start = tab(plan, t.kv_start); a.n = plan->n;
     int64_t tq = 0, tkv = 0;

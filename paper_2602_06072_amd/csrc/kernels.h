@@ -41,13 +41,35 @@ int launch_decode_f32(const DecodeArgs& a, void* stream);
 struct PrefillArgs {
     const void* q; const void* k; const void* v; void* out;
     const int32_t* tiles; int32_t n_tiles;
-    const int32_t* row_q; const int32_t* row_lo; const int32_t* row_hi;
+    const int32_t* run_first; const int32_t* runs;   // rows of a tile beyond its first run of consecutive rows
     const int32_t* kvtiles;
     const int32_t* q_start; const int32_t* kv_start; int32_t n;
     int64_t total_q_rows; int64_t total_kv_rows;
     int Hq; int Hkv; int d; float scale; int out_f32;
     int xcd_swizzle;                                // 1: place the heads of a KV head on one XCD
 };
+#if defined(__HIPCC__)
+// Row `local` (0..127) of query tile `tile`: its Q row (-1: padding) and its key range [lo, hi).
+// d4..d7 are words 4..7 of the tile's descriptor (rows | runs << 16; Q row, lo, hi of tile row 0).
+// A run is a stretch of consecutive rows of one request: inside it the Q row and hi advance by one
+// per row.  Tiles of one run (nearly all) need nothing but the descriptor.
+__device__ __forceinline__ void prefill_tile_row(const PrefillArgs& a, int tile, int d4, int d5, int d6, int d7,
+                                                 int local, int& qrow, int& lo, int& hi) {
+    const int n_rows = d4 & 0xFFFF, n_runs = d4 >> 16;
+    int begin = 0, q0 = d5, l0 = d6, h0 = d7;
+    if (n_runs > 1) {                               // uniform: a packed tile that holds several requests
+        const int32_t* rp = a.runs + 4 * static_cast<int64_t>(a.run_first[tile]);
+        for (int r = 1; r < n_runs; ++r, rp += 4) {
+            const int rb = rp[0];
+            if (local >= rb) { begin = rb; q0 = rp[1]; l0 = rp[2]; h0 = rp[3]; }
+        }
+    }
+    const bool valid = local < n_rows;
+    qrow = valid ? q0 + (local - begin) : -1;
+    lo = valid ? l0 : 0;
+    hi = valid ? h0 + (local - begin) : 0;
+}
+#endif
 int launch_prefill_bf16(const PrefillArgs& a, void* stream);
 int launch_prefill_f32(const PrefillArgs& a, void* stream);
 

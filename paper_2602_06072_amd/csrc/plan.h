@@ -67,8 +67,9 @@ struct DeviceTables {
     // prefill (packed and padded schedules share one format)
     struct PrefillSched {
         TableRef tiles;             // [n_tiles][8] kv_first, n_kv, leading / trailing skipped key tiles per wave (4 x 8 bits each),
-                                    // first Q row of a contiguous tile or -1, rows, 0, 0
-        TableRef row_q, row_lo, row_hi;   // [n_tiles*BM]
+                                    // rows | runs << 16, then Q row, lo, hi of tile row 0 (the first run)
+        TableRef run_first;         // [n_tiles] first entry of the tile's further runs
+        TableRef runs;              // (first tile row, its Q row, lo, its hi) of the runs after a tile's first
         TableRef kvtiles;           // [n_kv_total][2] k_start, n | wavemask<<8 | full<<16
         int32_t n_tiles = 0;
         int64_t issued_pairs = 0;

@@ -62,8 +62,8 @@ __global__ __launch_bounds__(256, 2) void prefill_bf16_kernel(PrefillArgs a) {
     if (n_kv == 0) return;
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 31, hlf = lane >> 5;
-    const int rr = tile * BM + wave * 32 + n;
-    const int qrow = a.row_q[rr], lo = a.row_lo[rr], hi = a.row_hi[rr];
+    int qrow, lo, hi;
+    prefill_tile_row(a, tile, desc[4], desc[5], desc[6], desc[7], wave * 32 + n, qrow, lo, hi);
 
     // ---- Q operand: lane (n, hlf) holds Q[row n][16s + 8hlf .. +8] ----------
     bf16x8 qf[KS];

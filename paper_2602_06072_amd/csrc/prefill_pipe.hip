@@ -67,7 +67,9 @@ __device__ __forceinline__ bool setup(const PrefillArgs& a, WorkUnit& u, LaneOff
     } else {
         tile = blockIdx.x / a.Hq; u.head = blockIdx.x % a.Hq; u.kvh = u.head / r;
     }
-    const int32_t* desc = a.tiles + 8 * static_cast<int64_t>(tile);
+    // everything about the tile in one 32-byte scalar load
+    typedef int32_t i32x8 __attribute__((ext_vector_type(8)));
+    const i32x8 desc = *(const __attribute__((address_space(4))) i32x8*)(a.tiles + 8 * static_cast<int64_t>(tile));
     u.n_kv = desc[1];
     if (u.n_kv == 0) return false;
     u.kvt = a.kvtiles + 2 * static_cast<int64_t>(desc[0]);
@@ -76,12 +78,7 @@ __device__ __forceinline__ bool setup(const PrefillArgs& a, WorkUnit& u, LaneOff
     u.wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     u.n_active = u.n_kv - ((desc[3] >> (8 * u.wave)) & 0xFF);
     u.n_lead = min((desc[2] >> (8 * u.wave)) & 0xFF, u.n_active);
-    const int rr = tile * BM + u.wave * 32 + u.n;
-    // a tile whose rows are one run of consecutive Q rows says so: no look-up ahead of the Q loads
-    const int q_first = desc[4], local = u.wave * 32 + u.n;
-    if (q_first >= 0) u.qrow = local < desc[5] ? q_first + local : -1;
-    else u.qrow = a.row_q[rr];
-    u.lo = a.row_lo[rr]; u.hi = a.row_hi[rr];
+    prefill_tile_row(a, tile, desc[4], desc[5], desc[6], desc[7], u.wave * 32 + u.n, u.qrow, u.lo, u.hi);
     u.row_bytes = static_cast<int64_t>(a.Hkv) * ROWB;
     u.row_bytes32 = static_cast<uint32_t>(a.Hkv) * ROWB;
     u.total_rows32 = static_cast<uint32_t>(a.total_kv_rows);

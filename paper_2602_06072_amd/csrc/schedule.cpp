@@ -213,7 +213,8 @@ struct QRow { int32_t req, t; };       // packed row -> (request, query position
 
 // Flat arrays of a schedule under construction (tiles in construction order).
 struct SchedBuild {
-    std::vector<int32_t> row_q, row_lo, row_hi;   // BM entries per tile
+    std::vector<int32_t> runs;                    // (first tile row, its Q row, lo, its hi) of every run of rows of one request
+    std::vector<int32_t> run_first, n_runs;       // per tile
     std::vector<int32_t> kv;                      // (k_start, info) pairs of all tiles
     std::vector<int32_t> kv_first, n_kv, n_rows;  // per tile
     std::vector<int64_t> weight;                  // active (wave, key tile) pairs per tile
@@ -226,15 +227,7 @@ void add_tile(const pk_plan& plan, const std::vector<int64_t>& q_start,
               const std::vector<int64_t>& kv_start, const QRow* rows, int nrows,
               bool all_waves, SchedBuild& sb) {
     constexpr int BM = kPrefillBM, BN = kPrefillBN, WR = 32, NW = BM / WR;
-    const size_t r0 = sb.row_q.size();
-    sb.row_q.resize(r0 + BM, -1); sb.row_lo.resize(r0 + BM, 0); sb.row_hi.resize(r0 + BM, 0);
-    for (int i = 0; i < nrows; ++i) {
-        const int32_t rq = rows[i].req;
-        const int64_t ctx = plan.kv_lens[rq] - plan.q_lens[rq];
-        sb.row_q[r0 + i] = static_cast<int32_t>(q_start[rq] + rows[i].t);
-        sb.row_lo[r0 + i] = static_cast<int32_t>(kv_start[rq]);
-        sb.row_hi[r0 + i] = static_cast<int32_t>(kv_start[rq] + ctx + rows[i].t + 1);
-    }
+    sb.run_first.push_back(static_cast<int32_t>(sb.runs.size() / 4));
     const size_t kv0 = sb.kv.size();
     int64_t weight = 0;
     int i = 0;
@@ -245,6 +238,11 @@ void add_tile(const pk_plan& plan, const std::vector<int64_t>& q_start,
         const int64_t ks0 = kv_start[rq];
         const int64_t ctx = plan.kv_lens[rq] - plan.q_lens[rq];
         const int64_t kend = ks0 + ctx + rows[j - 1].t + 1;              // hi of the run's last row
+        // row x of the run is Q row q_start + t + (x - i) and sees the keys [ks0, ks0 + ctx + t + 1 + (x - i))
+        sb.runs.push_back(i);
+        sb.runs.push_back(static_cast<int32_t>(q_start[rq] + rows[i].t));
+        sb.runs.push_back(static_cast<int32_t>(ks0));
+        sb.runs.push_back(static_cast<int32_t>(ks0 + ctx + rows[i].t + 1));
         // per wave: its rows inside the run, and whether it holds rows of no other request
         int wa[NW], wb[NW];
         bool pure[NW];
@@ -277,13 +275,13 @@ void add_tile(const pk_plan& plan, const std::vector<int64_t>& q_start,
     sb.kv_first.push_back(static_cast<int32_t>(kv0 / 2));
     sb.n_kv.push_back(static_cast<int32_t>((sb.kv.size() - kv0) / 2));
     sb.n_rows.push_back(nrows);
+    sb.n_runs.push_back(static_cast<int32_t>(sb.runs.size() / 4) - sb.run_first.back());
     sb.weight.push_back(weight);
 }
 
 void add_idle_tile(SchedBuild& sb) {               // padded grid slot of a request without that many tiles
-    sb.row_q.resize(sb.row_q.size() + kPrefillBM, -1);
-    sb.row_lo.resize(sb.row_lo.size() + kPrefillBM, 0);
-    sb.row_hi.resize(sb.row_hi.size() + kPrefillBM, 0);
+    sb.run_first.push_back(static_cast<int32_t>(sb.runs.size() / 4));
+    sb.n_runs.push_back(0);
     sb.kv_first.push_back(static_cast<int32_t>(sb.kv.size() / 2));
     sb.n_kv.push_back(0); sb.n_rows.push_back(0); sb.weight.push_back(0);
 }
@@ -291,10 +289,9 @@ void add_idle_tile(SchedBuild& sb) {               // padded grid slot of a requ
 // Writes the tiles in the given order (key-tile lists are re-based accordingly).
 void emit_sched(const SchedBuild& sb, const std::vector<int32_t>& order, Builder& b,
                 DeviceTables::PrefillSched& s) {
-    constexpr int BM = kPrefillBM;
-    std::vector<int32_t> desc, rq, rlo, rhi, kv;
+    std::vector<int32_t> desc, more_first, more, kv;
     desc.reserve(order.size() * 8);
-    rq.reserve(sb.row_q.size()); rlo.reserve(sb.row_q.size()); rhi.reserve(sb.row_q.size());
+    more_first.reserve(order.size());
     kv.reserve(sb.kv.size());
     for (int32_t idx : order) {
         desc.push_back(static_cast<int32_t>(kv.size() / 2));
@@ -315,24 +312,21 @@ void emit_sched(const SchedBuild& sb, const std::vector<int32_t>& order, Builder
         }
         desc.push_back(leading);
         desc.push_back(trailing);
-        // the rows of most tiles are one run of consecutive rows of Q: then the kernel needs no
-        // row_q look-up before it can fetch its Q operand (first row, or -1 if they are not)
-        int32_t q_first = sb.n_rows[idx] > 0 ? sb.row_q[static_cast<size_t>(idx) * BM] : -1;
-        for (int32_t x = 0; x < sb.n_rows[idx] && q_first >= 0; ++x)
-            if (sb.row_q[static_cast<size_t>(idx) * BM + x] != q_first + x) q_first = -1;
-        desc.push_back(q_first);
-        desc.push_back(sb.n_rows[idx]);
-        desc.push_back(0);
-        desc.push_back(0);
-        rq.insert(rq.end(), sb.row_q.begin() + idx * BM, sb.row_q.begin() + (idx + 1) * BM);
-        rlo.insert(rlo.end(), sb.row_lo.begin() + idx * BM, sb.row_lo.begin() + (idx + 1) * BM);
-        rhi.insert(rhi.end(), sb.row_hi.begin() + idx * BM, sb.row_hi.begin() + (idx + 1) * BM);
+        // The rows of a tile are runs of consecutive rows of one request each; most tiles are one
+        // run, which sits in the descriptor itself (its Q row, lo, hi of tile row 0): the kernel
+        // needs no second look-up before it can fetch its Q operand.  Further runs go to a list.
+        const int32_t nr = sb.n_runs[idx];
+        const int32_t* run = sb.runs.data() + 4 * static_cast<size_t>(sb.run_first[idx]);
+        desc.push_back(sb.n_rows[idx] | (nr << 16));
+        for (int x = 1; x < 4; ++x) desc.push_back(nr > 0 ? run[x] : 0);
+        more_first.push_back(static_cast<int32_t>(more.size() / 4));
+        if (nr > 1) more.insert(more.end(), run + 4, run + 4 * static_cast<size_t>(nr));
         kv.insert(kv.end(), sb.kv.begin() + 2 * sb.kv_first[idx], sb.kv.begin() + 2 * (sb.kv_first[idx] + sb.n_kv[idx]));
     }
     s.n_tiles = static_cast<int32_t>(order.size());
     s.issued_pairs = sb.issued;
     s.tiles = b.add(desc);
-    s.row_q = b.add(rq); s.row_lo = b.add(rlo); s.row_hi = b.add(rhi);
+    s.run_first = b.add(more_first); s.runs = b.add(more);
     s.kvtiles = b.add(kv);
 }
 
@@ -441,7 +435,7 @@ size_t padded_bound_bytes(const pk_plan& plan) {
             kv_entries += (ctx + std::min<int64_t>(plan.q_lens[i], (tt + 1) * BM) + BN - 1) / BN;
     }
     const int64_t tiles = max_tiles * plan.n;
-    const int64_t ints = tiles * 8 + 3 * tiles * BM + 2 * kv_entries + 6 * 64;
+    const int64_t ints = tiles * 8 + tiles + 2 * kv_entries + 6 * 64;   // a padded tile is one run: the run list is empty
     return static_cast<size_t>((ints + 63) / 64 * 64) * sizeof(int32_t);
 }
 
