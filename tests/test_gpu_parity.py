@@ -255,3 +255,42 @@ def test_config5_mixed_step_sampled():
     wantd = H.oracle_paged_decode(d, False, reqs)
     H.assert_close(gotd[reqs], wantd, 0, "cfg5 decode")
     assert np.all(np.isfinite(gotd))
+
+
+def test_config5_full_size_sampled():
+    """Configuration 5 at the size bench.py runs (32 chunks with context, 480 decode requests,
+    17.7 GB of K/V): sampled prefill rows and sampled decode requests against the oracle."""
+    w = wl.config5(0, device=DEV)
+    p = w.prefill
+    plan = pk.pack_plan(p.kv_lens, p.q_lens, token_budget=p.token_budget)
+    ws = pk.new_workspace(plan, p.Hq, p.Hkv, p.d, pk.PK_BF16)
+    out = torch.full(p.q.shape, float("nan"), dtype=torch.bfloat16, device=DEV)
+    pk.packed_prefill_attn(plan, p.q, p.k, p.v, out, p.scale, ws)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(3)
+    rows = []
+    for i in _sample_requests(p.q_lens, rng, k=5):
+        L = int(p.q_lens[i])
+        for t in (0, L - 1, int(rng.integers(0, L))):
+            rows.append((int(i), int(rng.integers(0, p.Hq)), t))
+    qs = p.q_start
+    idx = torch.tensor([qs[i] + t for (i, h, t) in rows], device=DEV)
+    hh = torch.tensor([h for (i, h, t) in rows], device=DEV)
+    sel = out[idx, hh].float().cpu().numpy()
+    assert bool(torch.isfinite(out.float()).all())
+    H.assert_close(sel, H.oracle_ragged(p, False, rows=rows), 0, "cfg5 full prefill sampled rows")
+    del out, ws, plan
+    d = w.decode
+    ones = np.ones_like(d.kv_lens)
+    pland = pk.pack_plan(d.kv_lens, ones, d.prefix_ids, d.prefix_lens, d.token_budget, 0)
+    wsd = pk.new_workspace(pland, d.Hq, d.Hkv, d.d, pk.PK_BF16)
+    pk.plan_bind(pland, d.Hq, d.Hkv, d.d, pk.PK_BF16, wsd)
+    buf = pk.new_kv_buf(pland, d.Hkv, d.d, pk.PK_BF16)
+    pk.kv_reorganize(pland, d.k_pages, d.v_pages, torch.from_numpy(d.block_table).to(DEV), buf, wsd)
+    outd = torch.full(d.q.shape, float("nan"), dtype=torch.float32, device=DEV)
+    pk.packed_decode_attn(pland, d.q, buf, outd, d.scale, d.Hkv, wsd)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(outd).all())
+    reqs = _sample_requests(d.kv_lens, rng, k=6)
+    H.assert_close(outd[torch.as_tensor(np.asarray(reqs), device=DEV)].cpu().numpy(),
+                   H.oracle_paged_decode(d, False, reqs), 0, "cfg5 full decode")
