@@ -126,3 +126,44 @@ def test_grown_zero_equals_plain_decode():
     pk.packed_decode_attn_grown(plan, w.q, kv_buf, b, w.scale, 0, w.Hkv, ws)
     torch.cuda.synchronize()
     assert torch.equal(a, b)
+
+
+def test_config3_full_size_32_steps_sampled():
+    """Configuration 3 at full size with the 32 slots of headroom bench.py uses: 32 appended tokens
+    per request, attention after the first and after the last step on sampled requests."""
+    w = wl.config3(0, device=DEV)
+    steps = 32
+    ones = np.ones(w.n, dtype=np.int32)
+    plan = pk.pack_plan(w.kv_lens, ones, w.prefix_ids, w.prefix_lens, w.token_budget, steps)
+    ws = pk.new_workspace(plan, w.Hq, w.Hkv, w.d, pk.PK_BF16)
+    kv_buf = pk.new_kv_buf(plan, w.Hkv, w.d, pk.PK_BF16)
+    pk.kv_reorganize(plan, w.k_pages, w.v_pages, torch.from_numpy(w.block_table).to(DEV), kv_buf, ws)
+    order = np.argsort(w.kv_lens)
+    reqs = sorted({int(order[0]), int(order[-1]), int(order[len(order) // 2]), 7, 100, 201})
+    base_kv = {i: logical(w, False, i) for i in reqs}
+    gen = torch.Generator(device=DEV).manual_seed(17)
+    app_k, app_v = [], []
+    for step in range(steps):
+        k_new = torch.randn((w.n, w.Hkv, w.d), generator=gen, device=DEV).to(torch.bfloat16)
+        v_new = torch.randn((w.n, w.Hkv, w.d), generator=gen, device=DEV).to(torch.bfloat16)
+        app_k.append(k_new[reqs].float().cpu().numpy())
+        app_v.append(v_new[reqs].float().cpu().numpy())
+        pk.kv_append(plan, k_new, v_new, kv_buf, step, ws)
+        if step not in (0, steps - 1):
+            continue
+        q_step = torch.randn(w.q.shape, generator=gen, device=DEV).to(torch.bfloat16)
+        out = torch.full(w.q.shape, float("nan"), dtype=torch.float32, device=DEV)
+        pk.packed_decode_attn_grown(plan, q_step, kv_buf, out, w.scale, step + 1, w.Hkv, ws)
+        torch.cuda.synchronize()
+        assert bool(torch.isfinite(out).all())
+        got = out[torch.as_tensor(reqs, device=DEV)].cpu().numpy()
+        qn = q_step[torch.as_tensor(reqs, device=DEV)].float().cpu().numpy()
+        ks, vs, lens = [], [], []
+        for x, i in enumerate(reqs):
+            K = np.concatenate([base_kv[i][0]] + [app_k[s][x:x + 1] for s in range(step + 1)])
+            V = np.concatenate([base_kv[i][1]] + [app_v[s][x:x + 1] for s in range(step + 1)])
+            ks.append(K); vs.append(V); lens.append(K.shape[0])
+        want, _ = oa.attention_ragged(qn, np.concatenate(ks), np.concatenate(vs), [1] * len(reqs), lens, w.scale)
+        H.assert_close(got, want, 0, f"cfg3 full size, step {step}")
+    flags, _ = pk.regroup_due(plan, steps)
+    assert flags & pk.REGROUP_HEADROOM
