@@ -277,6 +277,7 @@ int decode_common(const char* who, pk_plan* plan, const void* q, const void* kv_
     a.buf_tokens = plan->buf_tokens; a.n = plan->n;
     a.Hq = Hq; a.Hkv = Hkv; a.d = d; a.scale = scale; a.out_f32 = out_dtype == PK_F32;
     a.grown = grown;
+    a.max_parts = t.dec_max_parts;
     const int e = dtype == PK_BF16 ? launch_decode_bf16(a, stream) : launch_decode_f32(a, stream);
     return e ? hip_fail(who, e) : PK_OK;
 }

@@ -190,15 +190,16 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
 }
 
 // out[i, h, :] = sum_j exp(lse_j - lse) o_j over the request's partial slots (consecutive).
-// Workgroup = (request, head), 4 waves; wave w takes slots w, w+4, ... four at a time (all
-// loads of a batch are issued before the first use), every lane owns D/64 columns; the four
-// partial sums meet in LDS.  Requests with a single work item were written by the decode
-// kernel and are skipped.
-template <int D>
-__global__ __launch_bounds__(256) void decode_merge_kernel(DecodeArgs a) {
+// Workgroup = (request, head), WAVES waves; wave w takes slots w, w + WAVES, ... four at a time
+// (all loads of a batch are issued before the first use), every lane owns D/64 columns; with
+// more than one wave the partial sums meet in LDS.  One wave is enough when no request has more
+// than a handful of partial results (short launches then end sooner).  Requests with a single
+// work item were written by the decode kernel and are skipped.
+template <int D, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void decode_merge_kernel(DecodeArgs a) {
     constexpr int CPL = D / 64;                    // columns per lane
-    __shared__ float red_acc[4][D];
-    __shared__ float red_tot[4];
+    __shared__ float red_acc[WAVES][D];
+    __shared__ float red_tot[WAVES];
     const int i = blockIdx.x, h = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int p0 = a.req_part_start[i], p1 = a.req_part_start[i + 1];
     if (p1 <= p0) return;
@@ -209,11 +210,11 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(DecodeArgs a) {
     float acc[CPL], tot = 0.f;
 #pragma unroll
     for (int c = 0; c < CPL; ++c) acc[c] = 0.f;
-    for (int p = p0 + wave; p < p1; p += 16) {
+    for (int p = p0 + wave; p < p1; p += 4 * WAVES) {
         float lse[4], v[4][CPL];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const int q = p + 4 * u;
+            const int q = p + WAVES * u;
             lse[u] = q < p1 ? lse_base[static_cast<int64_t>(q) * a.Hq] : -INFINITY;
 #pragma unroll
             for (int c = 0; c < CPL; ++c)
@@ -227,20 +228,29 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(DecodeArgs a) {
             for (int c = 0; c < CPL; ++c) acc[c] = fmaf(w, v[u][c], acc[c]);
         }
     }
+    if constexpr (WAVES > 1) {
 #pragma unroll
-    for (int c = 0; c < CPL; ++c) red_acc[wave][lane * CPL + c] = acc[c];
-    if (lane == 0) red_tot[wave] = tot;
-    __syncthreads();
-    if (wave != 0) return;
-    tot = red_tot[0] + red_tot[1] + red_tot[2] + red_tot[3];
+        for (int c = 0; c < CPL; ++c) red_acc[wave][lane * CPL + c] = acc[c];
+        if (lane == 0) red_tot[wave] = tot;
+        __syncthreads();
+        if (wave != 0) return;
+        tot = 0.f;
+#pragma unroll
+        for (int w = 0; w < WAVES; ++w) tot += red_tot[w];
+#pragma unroll
+        for (int c = 0; c < CPL; ++c) {
+            acc[c] = 0.f;
+#pragma unroll
+            for (int w = 0; w < WAVES; ++w) acc[c] += red_acc[w][lane * CPL + c];
+        }
+    }
     const float inv = tot > 0.f ? 1.f / tot : 0.f;
 #pragma unroll
     for (int c = 0; c < CPL; ++c) {
         const int col = lane * CPL + c;
-        const float o = (red_acc[0][col] + red_acc[1][col] + red_acc[2][col] + red_acc[3][col]) * inv;
         const int64_t dst = (static_cast<int64_t>(i) * a.Hq + h) * D + col;
-        if (a.out_f32) static_cast<float*>(a.out)[dst] = o;
-        else static_cast<uint16_t*>(a.out)[dst] = float_to_bf16_bits(o);
+        if (a.out_f32) static_cast<float*>(a.out)[dst] = acc[c] * inv;
+        else static_cast<uint16_t*>(a.out)[dst] = float_to_bf16_bits(acc[c] * inv);
     }
 }
 
@@ -251,9 +261,11 @@ int launch_d(const DecodeArgs& a, hipStream_t st) {
         if (a.n_wide > 0) hipLaunchKernelGGL(decode_bf16_mixed_kernel<D>, grid, dim3(64), 0, st, a);
         else hipLaunchKernelGGL(decode_bf16_kernel<D>, grid, dim3(64), 0, st, a);
     }
-    if (a.n > 0)
-        hipLaunchKernelGGL(decode_merge_kernel<D>, dim3(static_cast<unsigned>(a.n), static_cast<unsigned>(a.Hq)),
-                           dim3(256), 0, st, a);
+    if (a.n > 0 && a.max_parts > 0) {
+        const dim3 mgrid(static_cast<unsigned>(a.n), static_cast<unsigned>(a.Hq));
+        if (a.max_parts <= 8) hipLaunchKernelGGL((decode_merge_kernel<D, 1>), mgrid, dim3(64), 0, st, a);
+        else hipLaunchKernelGGL((decode_merge_kernel<D, 4>), mgrid, dim3(256), 0, st, a);
+    }
     return static_cast<int>(hipGetLastError());
 }
 

@@ -34,6 +34,7 @@ struct DecodeArgs {
     float* part_o; float* part_lse;
     int64_t buf_tokens; int32_t n; int Hq; int Hkv; int d; float scale; int out_f32;
     int32_t grown;                                  // tokens appended to every suffix since the plan was made
+    int32_t max_parts;                              // most partial results of one request
 };
 int launch_decode_bf16(const DecodeArgs& a, void* stream);
 int launch_decode_f32(const DecodeArgs& a, void* stream);

@@ -63,6 +63,7 @@ struct DeviceTables {
     TableRef dec_chain_start;       // [n+1] first entry of each request in dec_chain
     TableRef dec_chain;             // (absolute offset, tokens) of a request's shared segments, outermost first
     int32_t n_dec_items = 0, n_dec_wide = 0, n_dec_parts = 0, dec_split_tokens = 0;
+    int32_t dec_max_parts = 0;      // most partial results of one request
     int32_t pad_split_tokens = 0, pad_n_splits = 0;   // padded decode comparison: uniform splits
     // prefill (packed and padded schedules share one format)
     struct PrefillSched {

@@ -199,6 +199,8 @@ void build_decode(const pk_plan& plan, int Hq, int Hkv, Builder& b, DeviceTables
     }
     t.n_dec_items = static_cast<int32_t>(items.size());
     t.n_dec_parts = n_parts;
+    t.dec_max_parts = 0;
+    for (int32_t c : n_items_of) t.dec_max_parts = std::max(t.dec_max_parts, c > 1 ? c : 0);
     t.dec_items = b.add(flat);
     t.dec_members = b.add(members);
     t.dec_member_slot = b.add(member_slot);
