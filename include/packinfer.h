@@ -30,10 +30,17 @@
  *     calls on ONE plan must not run concurrently from several host threads,
  *     and launches that share a workspace must be ordered on the stream(s)
  *     by the caller (decode keeps partial results there).  Different plans
- *     may be used from different threads.
+ *     may be used from different threads.  A workspace has ONE owner at a
+ *     time, the plan that bound it last: a compute call of another plan on
+ *     the same workspace uploads that plan's tables again (the library keeps
+ *     track of the last binder per workspace address).  The caller must not
+ *     write to, free or reuse the memory of a workspace while a plan that is
+ *     bound to it is still in use; after doing so, call pk_plan_bind, which
+ *     always uploads.
  *   - Return value: PK_OK (0) or a negative PK_E* code; the message is
  *     available from pk_last_error() (thread-local).  Arguments are checked
- *     before anything is launched.  Nothing throws or aborts.
+ *     before anything is launched.  Nothing throws or aborts: every entry
+ *     point catches host exceptions (PK_ENOMEM when host memory runs out).
  *   - dtype: PK_BF16 (MFMA path) or PK_F32 (plain-FMA debug path).
  *     out_dtype: PK_BF16 or PK_F32 for the attention outputs.
  */
@@ -223,8 +230,8 @@ int pk_packed_prefill_attn(pk_plan* plan, const void* q, const void* k, const vo
  *
  *   q    device [n][Hq][d]       kv_buf  device, as written by reorganize
  *   out  device [n][Hq][d], out_dtype
- * Errors: PK_EINVAL; PK_EUNSUPPORTED (bf16 path: d in {64,128}, Hq/Hkv in
- * {1,2,4,8,16}).
+ * Errors: PK_EINVAL; PK_EUNSUPPORTED (bf16 path: d in {64,128}, Hq/Hkv <= 32,
+ * any ratio; a work item carries 32 / (Hq/Hkv) requests of a shared prefix).
  */
 int pk_packed_decode_attn(pk_plan* plan, const void* q, const void* kv_buf,
                           void* out, float scale, int Hq, int Hkv, int d,
@@ -322,7 +329,8 @@ int pk_regroup_due(const pk_plan* plan, int32_t steps, int32_t* flags, int64_t* 
  *            every request's last tile is padded; natural request order.
  *   decode:  reads the PAGED pool through the block table, uniform number
  *            of splits sized by the longest request, shared prefixes re-read
- *            by every member.
+ *            by every member.  bf16 only, d in {64,128}, Hq/Hkv <= 16
+ *            (PK_EUNSUPPORTED otherwise).
  */
 int pk_padded_prefill_attn(pk_plan* plan, const void* q, const void* k, const void* v,
                            void* out, float scale, int Hq, int Hkv, int d,
@@ -336,14 +344,27 @@ int pk_padded_decode_attn(pk_plan* plan, const void* q,
                           int dtype, int out_dtype,
                           void* workspace, size_t workspace_bytes, void* stream);
 
-/* Counts for the benchmark's work accounting (host):
+/* Counts for the benchmark's work accounting (host).  1..7 refer to the
+ * tables of the head shape the plan was last sized or bound for (0 before).
  *   what = 0: unmasked (query,key) pairs per head summed over requests
  *   what = 1: (query,key) pairs issued to the MFMA units by the packed
  *             prefill schedule, per head
  *   what = 2: same for the padded prefill schedule
- *   what = 3: decode work items of the bound shape; 4: partial slots
+ *   what = 3: decode work items; 4: split-KV partial slots;
+ *   what = 5: tokens per decode split chosen by the schedule builder
+ *   what = 6: query tiles of the packed prefill schedule; 7: of the padded
  */
 int64_t pk_plan_stat(const pk_plan* plan, int what);
+
+/* Offline profiling of schedule parameters (Sec. 3.1: capacity and tile
+ * shapes are found by profiling a range of settings).  Overrides a choice of
+ * the schedule builder for this plan; the next pk_workspace_bytes /
+ * pk_plan_bind builds the tables again.  Results never depend on it.
+ *   PK_TUNE_DECODE_SPLIT  tokens per split-KV work item (rounded up to
+ *                         PK_KV_BLOCK); 0 = the builder's own choice
+ * Errors: PK_EINVAL (NULL plan, unknown knob, value out of range). */
+#define PK_TUNE_DECODE_SPLIT 0
+int pk_plan_tune(pk_plan* plan, int knob, int64_t value);
 
 /* Message of the last error on this thread ("" if none). */
 const char* pk_last_error(void);

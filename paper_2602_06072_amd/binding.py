@@ -78,6 +78,8 @@ def lib():
     L.pk_trie_tree.argtypes = [vp, vp, i32, i32, vp, vp, ctypes.POINTER(i32), vp, ctypes.POINTER(i64)]
     L.pk_trie_partition.restype = ci
     L.pk_trie_partition.argtypes = [vp, vp, i32, i32, vp, vp, ctypes.POINTER(i64)]
+    L.pk_plan_tune.restype = ci
+    L.pk_plan_tune.argtypes = [vp, ci, i64]
     L.pk_plan_stat.restype = i64
     L.pk_plan_stat.argtypes = [vp, ci]
     L.pk_last_error.restype = ctypes.c_char_p
@@ -93,8 +95,9 @@ EXPORTS = [
     "pk_kv_reorganize", "pk_packed_prefill_attn", "pk_packed_decode_attn",
     "pk_padded_prefill_attn", "pk_padded_decode_attn", "pk_plan_stat", "pk_last_error",
     "pk_kv_append", "pk_packed_decode_attn_grown", "pk_regroup_due", "pk_trie_partition",
-    "pk_pack_plan_tree", "pk_trie_tree",
+    "pk_pack_plan_tree", "pk_trie_tree", "pk_plan_tune",
 ]
+TUNE_DECODE_SPLIT = 0
 REGROUP_DRIFT, REGROUP_HEADROOM, REGROUP_DRIFT_WITHIN_BUDGET = 1, 2, 4
 
 
@@ -196,6 +199,10 @@ class Plan:
     def stat(self, what: int) -> int:
         return int(lib().pk_plan_stat(self._h, what))
 
+    def tune(self, knob: int, value: int) -> None:
+        _check(lib().pk_plan_tune(self._h, int(knob), int(value)), "pk_plan_tune")
+        self._ws = None
+
     def kv_buf_bytes(self, Hkv, d, dtype) -> int:
         return int(lib().pk_kv_buf_bytes(self._h, Hkv, d, dtype))
 
@@ -261,6 +268,7 @@ def kv_reorganize(plan: Plan, k_pages, v_pages, block_table, kv_buf, workspace, 
         page, nb, Hkv, d, _dtype_code(k_pages), _ptr(kv_buf), _ptr(workspace),
         workspace.numel() * workspace.element_size(), _stream(stream))
     _check(rc, "pk_kv_reorganize")
+    plan._ws = workspace                # the call may have bound the plan to it
 
 
 def _prefill(fn_name, plan, q, k, v, out, scale, workspace, stream):
@@ -271,6 +279,7 @@ def _prefill(fn_name, plan, q, k, v, out, scale, workspace, stream):
         _dtype_code(q), _dtype_code(out), _ptr(workspace),
         workspace.numel() * workspace.element_size(), _stream(stream))
     _check(rc, fn_name)
+    plan._ws = workspace
     return out
 
 
@@ -289,6 +298,7 @@ def packed_decode_attn(plan, q, kv_buf, out, scale, Hkv, workspace, stream=None)
         _dtype_code(q), _dtype_code(out), _ptr(workspace),
         workspace.numel() * workspace.element_size(), _stream(stream))
     _check(rc, "pk_packed_decode_attn")
+    plan._ws = workspace
     return out
 
 
@@ -299,6 +309,7 @@ def packed_decode_attn_grown(plan, q, kv_buf, out, scale, grown, Hkv, workspace,
         _dtype_code(q), _dtype_code(out), _ptr(workspace),
         workspace.numel() * workspace.element_size(), _stream(stream))
     _check(rc, "pk_packed_decode_attn_grown")
+    plan._ws = workspace
     return out
 
 
@@ -308,6 +319,7 @@ def kv_append(plan, k_new, v_new, kv_buf, step, workspace, stream=None):
         plan.handle, _ptr(k_new), _ptr(v_new), _ptr(kv_buf), int(step), Hkv, d, _dtype_code(k_new),
         _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
     _check(rc, "pk_kv_append")
+    plan._ws = workspace
     return kv_buf
 
 
@@ -359,4 +371,5 @@ def padded_decode_attn(plan, q, k_pages, v_pages, block_table, out, scale, works
         _dtype_code(q), _dtype_code(out), _ptr(workspace),
         workspace.numel() * workspace.element_size(), _stream(stream))
     _check(rc, "pk_padded_decode_attn")
+    plan._ws = workspace
     return out

@@ -5,6 +5,7 @@
 #include <initializer_list>
 #include <mutex>
 #include <string>
+#include <unordered_map>
 #include <vector>
 
 #include "kernels.h"
@@ -92,15 +93,48 @@ int copy_tables(void* dst, const void* src, size_t bytes, void* stream) {
     return static_cast<int>(e);
 }
 
+// Which bind wrote a workspace last.  A plan only skips the upload of its tables when it was the
+// last one to bind that workspace: two plans that take turns on one workspace through the compute
+// calls each find the other's stamp and upload again.  (What the caller does to the bytes of a
+// workspace behind the library's back cannot be seen here; pk_plan_bind always uploads.)
+std::mutex g_owner_mutex;
+std::unordered_map<const void*, uint64_t> g_owner;   // workspace -> stamp of its last bind
+uint64_t g_next_stamp = 1;
+
+bool owns_workspace(const pk_plan* plan, const void* workspace) {
+    std::lock_guard<std::mutex> lock(g_owner_mutex);
+    auto it = g_owner.find(workspace);
+    return it != g_owner.end() && it->second == plan->bound_stamp;
+}
+
+uint64_t claim_workspace(const void* workspace) {
+    std::lock_guard<std::mutex> lock(g_owner_mutex);
+    if (g_owner.size() > 4096) g_owner.clear();     // forgetting an owner only costs it an upload
+    return g_owner[workspace] = g_next_stamp++;
+}
+
+// Compute units of the current device (the decode schedule sizes its work items to fill them);
+// 256 when there is no device to ask (table sizes can be queried on a host without one).
+int device_cus() {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) {
+        (void)hipGetLastError();
+        return 256;
+    }
+    return cus;
+}
+
 // Makes sure the plan's device tables for this shape live in `workspace`.
 int ensure_bound(pk_plan* plan, int Hq, int Hkv, int d, int dtype, void* workspace,
                  size_t workspace_bytes, void* stream) {
     DeviceTables& t = plan->tables;
     const bool same_shape = t.Hq == Hq && t.Hkv == Hkv && t.d == d && t.dtype == dtype;
-    if (same_shape && plan->bound_ws == workspace && plan->bound_bytes == workspace_bytes) return PK_OK;
+    if (same_shape && plan->bound_ws == workspace && plan->bound_bytes == workspace_bytes &&
+        owns_workspace(plan, workspace)) return PK_OK;
     if (!workspace) return fail(PK_EINVAL, "workspace is NULL");
     if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0) return fail(PK_EINVAL, "workspace must be 256-byte aligned");
-    if (!same_shape) build_tables(*plan, Hq, Hkv, d, dtype, t);
+    if (!same_shape) build_tables(*plan, Hq, Hkv, d, dtype, device_cus(), t);
     if (workspace_bytes < t.total_bytes) return fail(PK_EINVAL, "workspace smaller than pk_workspace_bytes");
     if (t.tables_bytes) {
         const int e = copy_tables(workspace, t.host.data(), t.tables_bytes, stream);
@@ -108,6 +142,7 @@ int ensure_bound(pk_plan* plan, int Hq, int Hkv, int d, int dtype, void* workspa
     }
     plan->bound_ws = workspace;
     plan->bound_bytes = workspace_bytes;
+    plan->bound_stamp = claim_workspace(workspace);
     t.padded_uploaded = false;
     return PK_OK;
 }
@@ -135,59 +170,65 @@ const int32_t* tab(const pk_plan* plan, const TableRef& r, size_t base = 0) {
 }  // namespace
 
 extern "C" size_t pk_kv_buf_bytes(const pk_plan* plan, int Hkv, int d, int dtype) {
-    if (!plan || Hkv <= 0 || d <= 0) return 0;
-    return kv_buf_bytes(*plan, Hkv, d, dtype);
+    return pk::guarded<size_t>(size_t{0}, size_t{0}, "pk_kv_buf_bytes", [&]() -> size_t {
+        if (!plan || Hkv <= 0 || d <= 0) return 0;
+        return kv_buf_bytes(*plan, Hkv, d, dtype);
+    });
 }
 
 extern "C" size_t pk_workspace_bytes(const pk_plan* plan, int Hq, int Hkv, int d, int dtype) {
-    std::string why;
-    if (!plan || !shape_ok(Hq, Hkv, d, dtype, why)) return 0;
-    const DeviceTables& t = plan->tables;
-    if (t.Hq == Hq && t.Hkv == Hkv && t.d == d && t.dtype == dtype) return t.total_bytes;
-    DeviceTables tmp;
-    build_tables(*plan, Hq, Hkv, d, dtype, tmp);
-    // keep the tables: the bind that follows reuses them
-    const_cast<pk_plan*>(plan)->tables = std::move(tmp);
-    const_cast<pk_plan*>(plan)->bound_ws = nullptr;
-    return plan->tables.total_bytes;
+    return pk::guarded<size_t>(size_t{0}, size_t{0}, "pk_workspace_bytes", [&]() -> size_t {
+        std::string why;
+        if (!plan || !shape_ok(Hq, Hkv, d, dtype, why)) return 0;
+        const DeviceTables& t = plan->tables;
+        if (t.Hq == Hq && t.Hkv == Hkv && t.d == d && t.dtype == dtype) return t.total_bytes;
+        // the tables are a cache inside the plan (mutable): the bind that follows reuses them
+        build_tables(*plan, Hq, Hkv, d, dtype, device_cus(), plan->tables);
+        plan->bound_ws = nullptr;
+        return plan->tables.total_bytes;
+    });
 }
 
 extern "C" int pk_plan_bind(pk_plan* plan, int Hq, int Hkv, int d, int dtype,
                             void* workspace, size_t workspace_bytes, void* stream) {
-    std::string why;
-    if (!plan) return fail(PK_EINVAL, "pk_plan_bind: plan is NULL");
-    if (!shape_ok(Hq, Hkv, d, dtype, why)) return fail(PK_EINVAL, "pk_plan_bind: " + why);
-    plan->bound_ws = nullptr;                      // force the copy
-    return ensure_bound(plan, Hq, Hkv, d, dtype, workspace, workspace_bytes, stream);
+    return pk::guarded<int>(PK_ENOMEM, PK_EINVAL, "pk_plan_bind", [&]() -> int {
+        std::string why;
+        if (!plan) return fail(PK_EINVAL, "pk_plan_bind: plan is NULL");
+        if (!shape_ok(Hq, Hkv, d, dtype, why)) return fail(PK_EINVAL, "pk_plan_bind: " + why);
+        plan->bound_ws = nullptr;                      // force the copy
+        return ensure_bound(plan, Hq, Hkv, d, dtype, workspace, workspace_bytes, stream);
+    });
 }
 
 extern "C" int pk_kv_reorganize(pk_plan* plan, const void* k_pages, const void* v_pages,
                                 const int32_t* block_table, int32_t max_blocks_per_req,
                                 int32_t page_size, int64_t num_blocks, int Hkv, int d, int dtype,
                                 void* kv_buf, void* workspace, size_t workspace_bytes, void* stream) {
-    std::string why;
-    if (!plan) return fail(PK_EINVAL, "pk_kv_reorganize: plan is NULL");
-    if (plan->n == 0) return PK_OK;
-    if (!k_pages || !v_pages || !block_table || !kv_buf) return fail(PK_EINVAL, "pk_kv_reorganize: NULL pointer");
-    if (!aligned16({k_pages, v_pages, kv_buf})) return fail(PK_EINVAL, "pk_kv_reorganize: tensors must be 16-byte aligned");
-    if (page_size <= 0 || num_blocks <= 0) return fail(PK_EINVAL, "pk_kv_reorganize: page_size and num_blocks must be positive");
-    int Hq = plan->tables.Hkv == Hkv && plan->tables.d == d && plan->tables.dtype == dtype ? plan->tables.Hq : Hkv;
-    if (!shape_ok(Hq, Hkv, d, dtype, why)) return fail(PK_EINVAL, "pk_kv_reorganize: " + why);
-    if (dtype == PK_BF16 && d != 64 && d != 128) return fail(PK_EUNSUPPORTED, "pk_kv_reorganize: bf16 path needs d in {64,128}");
-    int32_t max_len = 0;
-    for (int32_t L : plan->kv_lens) max_len = L > max_len ? L : max_len;
-    if (static_cast<int64_t>(max_blocks_per_req) * page_size < max_len)
-        return fail(PK_EINVAL, "pk_kv_reorganize: max_blocks_per_req too small for the longest request");
-    int rc = ensure_bound(plan, Hq, Hkv, d, dtype, workspace, workspace_bytes, stream);
-    if (rc != PK_OK) return rc;
-    const DeviceTables& t = plan->tables;
-    ReorgArgs a{};
-    a.k_pages = k_pages; a.v_pages = v_pages; a.block_table = block_table;
-    a.max_blocks = max_blocks_per_req; a.page_size = page_size; a.num_blocks = num_blocks;
-    a.seg = tab(plan, t.reorg_seg); a.n_seg = t.n_reorg_seg; a.blk_first = tab(plan, t.reorg_blk_first);
-    a.kv_buf = kv_buf; a.buf_tokens = plan->buf_tokens; a.Hkv = Hkv; a.d = d;
-    const int e = dtype == PK_BF16 ? launch_reorg_bf16(a, stream) : launch_reorg_f32(a, stream);
-    return e ? hip_fail("pk_kv_reorganize", e) : PK_OK;
+    return pk::guarded<int>(PK_ENOMEM, PK_EINVAL, "pk_kv_reorganize", [&]() -> int {
+        std::string why;
+        if (!plan) return fail(PK_EINVAL, "pk_kv_reorganize: plan is NULL");
+        if (plan->n == 0) return PK_OK;
+        if (!k_pages || !v_pages || !block_table || !kv_buf) return fail(PK_EINVAL, "pk_kv_reorganize: NULL pointer");
+        if (!aligned16({k_pages, v_pages, kv_buf})) return fail(PK_EINVAL, "pk_kv_reorganize: tensors must be 16-byte aligned");
+        if (page_size <= 0 || num_blocks <= 0) return fail(PK_EINVAL, "pk_kv_reorganize: page_size and num_blocks must be positive");
+        int Hq = plan->tables.Hkv == Hkv && plan->tables.d == d && plan->tables.dtype == dtype ? plan->tables.Hq : Hkv;
+        if (!shape_ok(Hq, Hkv, d, dtype, why)) return fail(PK_EINVAL, "pk_kv_reorganize: " + why);
+        if (dtype == PK_BF16 && d != 64 && d != 128) return fail(PK_EUNSUPPORTED, "pk_kv_reorganize: bf16 path needs d in {64,128}");
+        int32_t max_len = 0;
+        for (int32_t L : plan->kv_lens) max_len = L > max_len ? L : max_len;
+        if (static_cast<int64_t>(max_blocks_per_req) * page_size < max_len)
+            return fail(PK_EINVAL, "pk_kv_reorganize: max_blocks_per_req too small for the longest request");
+        int rc = ensure_bound(plan, Hq, Hkv, d, dtype, workspace, workspace_bytes, stream);
+        if (rc != PK_OK) return rc;
+        const DeviceTables& t = plan->tables;
+        ReorgArgs a{};
+        a.k_pages = k_pages; a.v_pages = v_pages; a.block_table = block_table;
+        a.max_blocks = max_blocks_per_req; a.page_size = page_size; a.num_blocks = num_blocks;
+        a.seg = tab(plan, t.reorg_seg); a.n_seg = t.n_reorg_seg; a.blk_first = tab(plan, t.reorg_blk_first);
+        a.kv_buf = kv_buf; a.buf_tokens = plan->buf_tokens; a.Hkv = Hkv; a.d = d;
+        const int e = dtype == PK_BF16 ? launch_reorg_bf16(a, stream) : launch_reorg_f32(a, stream);
+        return e ? hip_fail("pk_kv_reorganize", e) : PK_OK;
+    });
 }
 
 static int prefill_common(pk_plan* plan, const void* q, const void* k, const void* v, void* out,
@@ -223,7 +264,7 @@ static int prefill_common(pk_plan* plan, const void* q, const void* k, const voi
     if (tkv > INT32_MAX) return fail(PK_EUNSUPPORTED, std::string(who) + ": more than 2^31 KV rows");
     a.total_q_rows = tq; a.total_kv_rows = tkv;
     a.Hq = Hq; a.Hkv = Hkv; a.d = d; a.scale = scale; a.out_f32 = out_dtype == PK_F32;
-    a.xcd_swizzle = padded ? 0 : 1;
+    a.xcd_swizzle = 1;             // both schedules: the r heads of a KV head share an XCD (and its L2)
     const int e = dtype == PK_BF16 ? launch_prefill_bf16(a, stream) : launch_prefill_f32(a, stream);
     return e ? hip_fail(who, e) : PK_OK;
 }
@@ -232,14 +273,18 @@ extern "C" int pk_packed_prefill_attn(pk_plan* plan, const void* q, const void* 
                                       void* out, float scale, int Hq, int Hkv, int d,
                                       int dtype, int out_dtype,
                                       void* workspace, size_t workspace_bytes, void* stream) {
-    return prefill_common(plan, q, k, v, out, scale, Hq, Hkv, d, dtype, out_dtype, workspace, workspace_bytes, stream, false);
+    return pk::guarded<int>(PK_ENOMEM, PK_EINVAL, "pk_packed_prefill_attn", [&]() -> int {
+        return prefill_common(plan, q, k, v, out, scale, Hq, Hkv, d, dtype, out_dtype, workspace, workspace_bytes, stream, false);
+    });
 }
 
 extern "C" int pk_padded_prefill_attn(pk_plan* plan, const void* q, const void* k, const void* v,
                                       void* out, float scale, int Hq, int Hkv, int d,
                                       int dtype, int out_dtype,
                                       void* workspace, size_t workspace_bytes, void* stream) {
-    return prefill_common(plan, q, k, v, out, scale, Hq, Hkv, d, dtype, out_dtype, workspace, workspace_bytes, stream, true);
+    return pk::guarded<int>(PK_ENOMEM, PK_EINVAL, "pk_padded_prefill_attn", [&]() -> int {
+        return prefill_common(plan, q, k, v, out, scale, Hq, Hkv, d, dtype, out_dtype, workspace, workspace_bytes, stream, true);
+    });
 }
 
 namespace {
@@ -288,66 +333,74 @@ extern "C" int pk_packed_decode_attn(pk_plan* plan, const void* q, const void* k
                                      void* out, float scale, int Hq, int Hkv, int d,
                                      int dtype, int out_dtype,
                                      void* workspace, size_t workspace_bytes, void* stream) {
-    return decode_common("pk_packed_decode_attn", plan, q, kv_buf, out, scale, 0, Hq, Hkv, d, dtype, out_dtype,
-                         workspace, workspace_bytes, stream);
+    return pk::guarded<int>(PK_ENOMEM, PK_EINVAL, "pk_packed_decode_attn", [&]() -> int {
+        return decode_common("pk_packed_decode_attn", plan, q, kv_buf, out, scale, 0, Hq, Hkv, d, dtype, out_dtype,
+                             workspace, workspace_bytes, stream);
+    });
 }
 
 extern "C" int pk_packed_decode_attn_grown(pk_plan* plan, const void* q, const void* kv_buf,
                                            void* out, float scale, int32_t grown, int Hq, int Hkv, int d,
                                            int dtype, int out_dtype,
                                            void* workspace, size_t workspace_bytes, void* stream) {
-    return decode_common("pk_packed_decode_attn_grown", plan, q, kv_buf, out, scale, grown, Hq, Hkv, d, dtype,
-                         out_dtype, workspace, workspace_bytes, stream);
+    return pk::guarded<int>(PK_ENOMEM, PK_EINVAL, "pk_packed_decode_attn_grown", [&]() -> int {
+        return decode_common("pk_packed_decode_attn_grown", plan, q, kv_buf, out, scale, grown, Hq, Hkv, d, dtype,
+                             out_dtype, workspace, workspace_bytes, stream);
+    });
 }
 
 extern "C" int pk_kv_append(pk_plan* plan, const void* k_new, const void* v_new, void* kv_buf,
                             int32_t step, int Hkv, int d, int dtype,
                             void* workspace, size_t workspace_bytes, void* stream) {
-    std::string why;
-    if (!plan) return fail(PK_EINVAL, "pk_kv_append: plan is NULL");
-    if (plan->n == 0) return PK_OK;
-    if (!plan->decode_only) return fail(PK_EINVAL, "pk_kv_append: the plan must have q_len == 1 for every request");
-    if (!k_new || !v_new || !kv_buf) return fail(PK_EINVAL, "pk_kv_append: NULL pointer");
-    if (!aligned16({k_new, v_new, kv_buf})) return fail(PK_EINVAL, "pk_kv_append: tensors must be 16-byte aligned");
-    if (step < 0 || step >= plan->headroom)
-        return fail(PK_EINVAL, "pk_kv_append: step must be in [0, headroom): no slot left, regroup");
-    int Hq = plan->tables.Hkv == Hkv && plan->tables.d == d && plan->tables.dtype == dtype ? plan->tables.Hq : Hkv;
-    if (!shape_ok(Hq, Hkv, d, dtype, why)) return fail(PK_EINVAL, "pk_kv_append: " + why);
-    if (dtype == PK_BF16 && d != 64 && d != 128) return fail(PK_EUNSUPPORTED, "pk_kv_append: bf16 path needs d in {64,128}");
-    int rc = ensure_bound(plan, Hq, Hkv, d, dtype, workspace, workspace_bytes, stream);
-    if (rc != PK_OK) return rc;
-    const DeviceTables& t = plan->tables;
-    AppendArgs a{};
-    a.k_new = k_new; a.v_new = v_new; a.kv_buf = kv_buf;
-    a.req_seg = tab(plan, t.dec_req_seg);
-    a.buf_tokens = plan->buf_tokens; a.n = plan->n; a.step = step; a.Hkv = Hkv; a.d = d;
-    const int e = dtype == PK_BF16 ? launch_append_bf16(a, stream) : launch_append_f32(a, stream);
-    return e ? hip_fail("pk_kv_append", e) : PK_OK;
+    return pk::guarded<int>(PK_ENOMEM, PK_EINVAL, "pk_kv_append", [&]() -> int {
+        std::string why;
+        if (!plan) return fail(PK_EINVAL, "pk_kv_append: plan is NULL");
+        if (plan->n == 0) return PK_OK;
+        if (!plan->decode_only) return fail(PK_EINVAL, "pk_kv_append: the plan must have q_len == 1 for every request");
+        if (!k_new || !v_new || !kv_buf) return fail(PK_EINVAL, "pk_kv_append: NULL pointer");
+        if (!aligned16({k_new, v_new, kv_buf})) return fail(PK_EINVAL, "pk_kv_append: tensors must be 16-byte aligned");
+        if (step < 0 || step >= plan->headroom)
+            return fail(PK_EINVAL, "pk_kv_append: step must be in [0, headroom): no slot left, regroup");
+        int Hq = plan->tables.Hkv == Hkv && plan->tables.d == d && plan->tables.dtype == dtype ? plan->tables.Hq : Hkv;
+        if (!shape_ok(Hq, Hkv, d, dtype, why)) return fail(PK_EINVAL, "pk_kv_append: " + why);
+        if (dtype == PK_BF16 && d != 64 && d != 128) return fail(PK_EUNSUPPORTED, "pk_kv_append: bf16 path needs d in {64,128}");
+        int rc = ensure_bound(plan, Hq, Hkv, d, dtype, workspace, workspace_bytes, stream);
+        if (rc != PK_OK) return rc;
+        const DeviceTables& t = plan->tables;
+        AppendArgs a{};
+        a.k_new = k_new; a.v_new = v_new; a.kv_buf = kv_buf;
+        a.req_seg = tab(plan, t.dec_req_seg);
+        a.buf_tokens = plan->buf_tokens; a.n = plan->n; a.step = step; a.Hkv = Hkv; a.d = d;
+        const int e = dtype == PK_BF16 ? launch_append_bf16(a, stream) : launch_append_f32(a, stream);
+        return e ? hip_fail("pk_kv_append", e) : PK_OK;
+    });
 }
 
 extern "C" int pk_regroup_due(const pk_plan* plan, int32_t steps, int32_t* flags, int64_t* drift) {
-    if (!plan || !flags) return fail(PK_EINVAL, "pk_regroup_due: NULL pointer");
-    if (steps < 0) return fail(PK_EINVAL, "pk_regroup_due: steps must be non-negative");
-    // [0]: all groups; [1]: without the groups opened for an item longer than C
-    int64_t lo[2] = {0, 0}, hi[2] = {0, 0};
-    bool first[2] = {true, true};
-    for (const Group& g : plan->groups) {
-        const int64_t load = g.load + static_cast<int64_t>(steps) * static_cast<int64_t>(g.members.size());
-        for (int k = 0; k < 2; ++k) {
-            if (k == 1 && g.load > plan->token_budget) continue;
-            if (first[k] || load < lo[k]) lo[k] = load;
-            if (first[k] || load > hi[k]) hi[k] = load;
-            first[k] = false;
+    return pk::guarded<int>(PK_ENOMEM, PK_EINVAL, "pk_regroup_due", [&]() -> int {
+        if (!plan || !flags) return fail(PK_EINVAL, "pk_regroup_due: NULL pointer");
+        if (steps < 0) return fail(PK_EINVAL, "pk_regroup_due: steps must be non-negative");
+        // [0]: all groups; [1]: without the groups opened for an item longer than C
+        int64_t lo[2] = {0, 0}, hi[2] = {0, 0};
+        bool first[2] = {true, true};
+        for (const Group& g : plan->groups) {
+            const int64_t load = g.load + static_cast<int64_t>(steps) * static_cast<int64_t>(g.members.size());
+            for (int k = 0; k < 2; ++k) {
+                if (k == 1 && g.load > plan->token_budget) continue;
+                if (first[k] || load < lo[k]) lo[k] = load;
+                if (first[k] || load > hi[k]) hi[k] = load;
+                first[k] = false;
+            }
         }
-    }
-    const int64_t dl = first[0] ? 0 : hi[0] - lo[0], dl_in = first[1] ? 0 : hi[1] - lo[1];
-    int32_t f = 0;
-    if (2 * static_cast<int64_t>(steps) * dl >= plan->token_budget) f |= PK_REGROUP_DRIFT;
-    if (steps >= plan->headroom) f |= PK_REGROUP_HEADROOM;
-    if (2 * static_cast<int64_t>(steps) * dl_in >= plan->token_budget) f |= PK_REGROUP_DRIFT_WITHIN_BUDGET;
-    *flags = f;
-    if (drift) *drift = dl;
-    return PK_OK;
+        const int64_t dl = first[0] ? 0 : hi[0] - lo[0], dl_in = first[1] ? 0 : hi[1] - lo[1];
+        int32_t f = 0;
+        if (2 * static_cast<int64_t>(steps) * dl >= plan->token_budget) f |= PK_REGROUP_DRIFT;
+        if (steps >= plan->headroom) f |= PK_REGROUP_HEADROOM;
+        if (2 * static_cast<int64_t>(steps) * dl_in >= plan->token_budget) f |= PK_REGROUP_DRIFT_WITHIN_BUDGET;
+        *flags = f;
+        if (drift) *drift = dl;
+        return PK_OK;
+    });
 }
 
 extern "C" int pk_padded_decode_attn(pk_plan* plan, const void* q,
@@ -357,54 +410,70 @@ extern "C" int pk_padded_decode_attn(pk_plan* plan, const void* q,
                                      void* out, float scale, int Hq, int Hkv, int d,
                                      int dtype, int out_dtype,
                                      void* workspace, size_t workspace_bytes, void* stream) {
-    std::string why;
-    if (!plan) return fail(PK_EINVAL, "pk_padded_decode_attn: plan is NULL");
-    if (plan->n == 0) return PK_OK;
-    if (!plan->decode_only) return fail(PK_EINVAL, "pk_padded_decode_attn: the plan must have q_len == 1 for every request");
-    if (!q || !k_pages || !v_pages || !block_table || !out) return fail(PK_EINVAL, "pk_padded_decode_attn: NULL pointer");
-    if (!aligned16({q, k_pages, v_pages, out})) return fail(PK_EINVAL, "pk_padded_decode_attn: tensors must be 16-byte aligned");
-    if (page_size <= 0 || num_blocks <= 0) return fail(PK_EINVAL, "pk_padded_decode_attn: page_size and num_blocks must be positive");
-    if (!shape_ok(Hq, Hkv, d, dtype, why)) return fail(PK_EINVAL, "pk_padded_decode_attn: " + why);
-    if (out_dtype != PK_BF16 && out_dtype != PK_F32) return fail(PK_EINVAL, "pk_padded_decode_attn: bad out_dtype");
-    if (dtype != PK_BF16) return fail(PK_EUNSUPPORTED, "pk_padded_decode_attn: bf16 only");
-    if (d != 64 && d != 128) return fail(PK_EUNSUPPORTED, "pk_padded_decode_attn: needs d in {64,128}");
-    if (Hq / Hkv > 16) return fail(PK_EUNSUPPORTED, "pk_padded_decode_attn: needs Hq/Hkv <= 16");
-    int32_t max_len = 0;
-    for (int32_t L : plan->kv_lens) max_len = L > max_len ? L : max_len;
-    if (static_cast<int64_t>(max_blocks_per_req) * page_size < max_len)
-        return fail(PK_EINVAL, "pk_padded_decode_attn: max_blocks_per_req too small for the longest request");
-    int rc = ensure_bound(plan, Hq, Hkv, d, dtype, workspace, workspace_bytes, stream);
-    if (rc != PK_OK) return rc;
-    const DeviceTables& t = plan->tables;
-    PagedDecodeArgs a{};
-    a.q = q; a.k_pages = k_pages; a.v_pages = v_pages; a.out = out;
-    a.block_table = block_table; a.max_blocks = max_blocks_per_req; a.page_size = page_size; a.num_blocks = num_blocks;
-    a.kv_start = tab(plan, t.kv_start);
-    a.n = plan->n; a.n_splits = t.pad_n_splits; a.split_tokens = t.pad_split_tokens;
-    a.part_o = reinterpret_cast<float*>(static_cast<char*>(workspace) + t.partial_offset);
-    a.part_lse = a.part_o + static_cast<size_t>(plan->n) * t.pad_n_splits * Hq * d;
-    a.Hq = Hq; a.Hkv = Hkv; a.d = d; a.scale = scale; a.out_f32 = out_dtype == PK_F32;
-    const int e = launch_padded_decode_bf16(a, stream);
-    return e ? hip_fail("pk_padded_decode_attn", e) : PK_OK;
+    return pk::guarded<int>(PK_ENOMEM, PK_EINVAL, "pk_padded_decode_attn", [&]() -> int {
+        std::string why;
+        if (!plan) return fail(PK_EINVAL, "pk_padded_decode_attn: plan is NULL");
+        if (plan->n == 0) return PK_OK;
+        if (!plan->decode_only) return fail(PK_EINVAL, "pk_padded_decode_attn: the plan must have q_len == 1 for every request");
+        if (!q || !k_pages || !v_pages || !block_table || !out) return fail(PK_EINVAL, "pk_padded_decode_attn: NULL pointer");
+        if (!aligned16({q, k_pages, v_pages, out})) return fail(PK_EINVAL, "pk_padded_decode_attn: tensors must be 16-byte aligned");
+        if (page_size <= 0 || num_blocks <= 0) return fail(PK_EINVAL, "pk_padded_decode_attn: page_size and num_blocks must be positive");
+        if (!shape_ok(Hq, Hkv, d, dtype, why)) return fail(PK_EINVAL, "pk_padded_decode_attn: " + why);
+        if (out_dtype != PK_BF16 && out_dtype != PK_F32) return fail(PK_EINVAL, "pk_padded_decode_attn: bad out_dtype");
+        if (dtype != PK_BF16) return fail(PK_EUNSUPPORTED, "pk_padded_decode_attn: bf16 only");
+        if (d != 64 && d != 128) return fail(PK_EUNSUPPORTED, "pk_padded_decode_attn: needs d in {64,128}");
+        if (Hq / Hkv > 16) return fail(PK_EUNSUPPORTED, "pk_padded_decode_attn: needs Hq/Hkv <= 16");
+        int32_t max_len = 0;
+        for (int32_t L : plan->kv_lens) max_len = L > max_len ? L : max_len;
+        if (static_cast<int64_t>(max_blocks_per_req) * page_size < max_len)
+            return fail(PK_EINVAL, "pk_padded_decode_attn: max_blocks_per_req too small for the longest request");
+        int rc = ensure_bound(plan, Hq, Hkv, d, dtype, workspace, workspace_bytes, stream);
+        if (rc != PK_OK) return rc;
+        const DeviceTables& t = plan->tables;
+        PagedDecodeArgs a{};
+        a.q = q; a.k_pages = k_pages; a.v_pages = v_pages; a.out = out;
+        a.block_table = block_table; a.max_blocks = max_blocks_per_req; a.page_size = page_size; a.num_blocks = num_blocks;
+        a.kv_start = tab(plan, t.kv_start);
+        a.n = plan->n; a.n_splits = t.pad_n_splits; a.split_tokens = t.pad_split_tokens;
+        a.part_o = reinterpret_cast<float*>(static_cast<char*>(workspace) + t.partial_offset);
+        a.part_lse = a.part_o + static_cast<size_t>(plan->n) * t.pad_n_splits * Hq * d;
+        a.Hq = Hq; a.Hkv = Hkv; a.d = d; a.scale = scale; a.out_f32 = out_dtype == PK_F32;
+        const int e = launch_padded_decode_bf16(a, stream);
+        return e ? hip_fail("pk_padded_decode_attn", e) : PK_OK;
+    });
+}
+
+extern "C" int pk_plan_tune(pk_plan* plan, int knob, int64_t value) {
+    return pk::guarded<int>(PK_ENOMEM, PK_EINVAL, "pk_plan_tune", [&]() -> int {
+        if (!plan) return fail(PK_EINVAL, "pk_plan_tune: plan is NULL");
+        if (knob != PK_TUNE_DECODE_SPLIT) return fail(PK_EINVAL, "pk_plan_tune: unknown knob");
+        if (value < 0 || value > (1 << 20)) return fail(PK_EINVAL, "pk_plan_tune: decode split must be in [0, 2^20] tokens");
+        plan->tune_decode_split = static_cast<int32_t>(value);
+        plan->tables = DeviceTables();                 // the next size query or bind builds the tables again
+        plan->bound_ws = nullptr;
+        return PK_OK;
+    });
 }
 
 extern "C" int64_t pk_plan_stat(const pk_plan* plan, int what) {
-    if (!plan) return 0;
-    switch (what) {
-        case 0: return plan->unmasked_pairs;
-        case 1: return plan->tables.packed.issued_pairs;
-        case 2:
-            if (!plan->tables.padded_built && plan->tables.dtype >= 0)
-                build_prefill_padded(*plan, const_cast<pk_plan*>(plan)->tables);
-            return plan->tables.padded.issued_pairs;
-        case 3: return plan->tables.n_dec_items;
-        case 4: return plan->tables.n_dec_parts;
-        case 5: return plan->tables.dec_split_tokens;
-        case 6: return plan->tables.packed.n_tiles;
-        case 7:
-            if (!plan->tables.padded_built && plan->tables.dtype >= 0)
-                build_prefill_padded(*plan, const_cast<pk_plan*>(plan)->tables);
-            return plan->tables.padded.n_tiles;
-        default: return 0;
-    }
+    return pk::guarded<int64_t>(int64_t{0}, int64_t{0}, "pk_plan_stat", [&]() -> int64_t {
+        if (!plan) return 0;
+        switch (what) {
+            case 0: return plan->unmasked_pairs;
+            case 1: return plan->tables.packed.issued_pairs;
+            case 2:
+                if (!plan->tables.padded_built && plan->tables.dtype >= 0)
+                    build_prefill_padded(*plan, plan->tables);
+                return plan->tables.padded.issued_pairs;
+            case 3: return plan->tables.n_dec_items;
+            case 4: return plan->tables.n_dec_parts;
+            case 5: return plan->tables.dec_split_tokens;
+            case 6: return plan->tables.packed.n_tiles;
+            case 7:
+                if (!plan->tables.padded_built && plan->tables.dtype >= 0)
+                    build_prefill_padded(*plan, plan->tables);
+                return plan->tables.padded.n_tiles;
+            default: return 0;
+        }
+    });
 }

@@ -3,6 +3,8 @@
 #pragma once
 #include <cstddef>
 #include <cstdint>
+#include <exception>
+#include <new>
 #include <string>
 #include <vector>
 
@@ -100,18 +102,40 @@ struct pk_plan {
     int64_t unique_tokens = 0;
     int64_t unmasked_pairs = 0;
     std::vector<int32_t> words;     // canonical serialisation
-    // binding state
-    pk::DeviceTables tables;
-    void* bound_ws = nullptr;
-    size_t bound_bytes = 0;
+    int32_t tune_decode_split = 0;  // pk_plan_tune: 0 = chosen by the schedule builder
+    // binding state: a cache of what was last built / uploaded for this plan, also filled by the
+    // size query on a const plan (calls on one plan are serialised by the caller)
+    mutable pk::DeviceTables tables;
+    mutable void* bound_ws = nullptr;
+    mutable size_t bound_bytes = 0;
+    uint64_t bound_stamp = 0;       // stamp of the bind that wrote bound_ws (0: none)
 };
 
 namespace pk {
 
 void set_error(const std::string& msg);
 
+// Exception barrier of the C ABI: nothing may unwind through an extern "C" entry point.  Host
+// containers can throw (std::bad_alloc, std::length_error); the entry point then reports an
+// error code and a message like any other failure.
+template <class R, class F>
+R guarded(R on_alloc, R on_other, const char* who, F&& body) noexcept {
+    try {
+        return body();
+    } catch (const std::bad_alloc&) {
+        try { set_error(std::string(who) + ": out of host memory"); } catch (...) {}
+        return on_alloc;
+    } catch (const std::exception& e) {
+        try { set_error(std::string(who) + ": " + e.what()); } catch (...) {}
+        return on_other;
+    } catch (...) {
+        try { set_error(std::string(who) + ": unknown failure"); } catch (...) {}
+        return on_other;
+    }
+}
+
 // schedule.cpp
-void build_tables(const pk_plan& plan, int Hq, int Hkv, int d, int dtype, DeviceTables& out);
+void build_tables(const pk_plan& plan, int Hq, int Hkv, int d, int dtype, int num_cus, DeviceTables& out);
 void build_prefill_padded(const pk_plan& plan, DeviceTables& t);
 size_t kv_buf_bytes(const pk_plan& plan, int Hkv, int d, int dtype);
 

@@ -16,6 +16,8 @@
 // This staged kernel serves head dimension 64; head dimension 128 runs the
 // direct-to-LDS kernel of prefill_pipe.hip (same tables, same arithmetic).
 
+#include <mutex>
+
 #include "common.hip.h"
 #include "kernels.h"
 
@@ -285,7 +287,9 @@ __global__ __launch_bounds__(256, 2) void prefill_bf16_kernel(PrefillArgs a) {
 
 template <int D>
 int launch_p(const PrefillArgs& a, hipStream_t st) {
+    static std::mutex attr_mutex;                   // plans may be used from several host threads
     static bool attr_set = false;
+    std::lock_guard<std::mutex> attr_lock(attr_mutex);
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(prefill_bf16_kernel<D>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, Smem<D>::TOTAL);

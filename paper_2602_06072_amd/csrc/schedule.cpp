@@ -8,7 +8,6 @@
 // whether that wave skips it, computes it with the mask, or computes it
 // without any mask.
 #include <algorithm>
-#include <cstdlib>
 #include <numeric>
 
 #include "plan.h"
@@ -29,13 +28,6 @@ struct Builder {
         return r;
     }
 };
-
-int env_int(const char* name, int dflt) {
-    const char* s = std::getenv(name);
-    if (!s || !*s) return dflt;
-    const int v = std::atoi(s);
-    return v > 0 ? v : dflt;
-}
 
 // ---- re-layout -------------------------------------------------------------
 void build_reorg(const pk_plan& plan, Builder& b, DeviceTables& t) {
@@ -68,7 +60,7 @@ void build_reorg(const pk_plan& plan, Builder& b, DeviceTables& t) {
 }
 
 // ---- decode ----------------------------------------------------------------
-void build_decode(const pk_plan& plan, int Hq, int Hkv, Builder& b, DeviceTables& t) {
+void build_decode(const pk_plan& plan, int Hq, int Hkv, int num_cus, Builder& b, DeviceTables& t) {
     const int r = Hq / Hkv;
     const int max_members = std::max(1, kDecodeMaxRows / r);
     // split length: about 1500 waves (work items x KV heads) keep enough loads in flight to fill
@@ -84,7 +76,7 @@ void build_decode(const pk_plan& plan, int Hq, int Hkv, Builder& b, DeviceTables
         bool wide = false;
         for (const Group& g : plan.groups)
             for (const Node& nd : g.nodes) wide = wide || static_cast<int>(std::min<size_t>(nd.reqs.size(), max_members)) * r > 16;
-        const int64_t capacity = (wide ? 8 : 16) * 256 * 9 / 10;
+        const int64_t capacity = static_cast<int64_t>(wide ? 8 : 16) * num_cus * 9 / 10;
         auto pieces_of = [&](int64_t len, int64_t sp) { return len <= 0 ? int64_t{0} : ((len + kDecodeBlock - 1) / kDecodeBlock * kDecodeBlock + sp - 1) / sp; };
         auto count_items = [&](int64_t sp) {
             int64_t c = 0;
@@ -98,7 +90,7 @@ void build_decode(const pk_plan& plan, int Hq, int Hkv, Builder& b, DeviceTables
         while (split < 2048 && count_items(split) * Hkv > capacity)
             split = std::min<int64_t>(2048, (split * 5 / 4 + kDecodeBlock - 1) / kDecodeBlock * kDecodeBlock);
     }
-    split = env_int("PK_DECODE_SPLIT", static_cast<int>(split));
+    if (plan.tune_decode_split > 0) split = plan.tune_decode_split;     // pk_plan_tune (profiling sweeps)
     split = (split + kDecodeBlock - 1) / kDecodeBlock * kDecodeBlock;
     t.dec_split_tokens = static_cast<int32_t>(split);
 
@@ -448,7 +440,7 @@ size_t kv_buf_bytes(const pk_plan& plan, int Hkv, int d, int dtype) {
     return static_cast<size_t>(plan.buf_tokens) * Hkv * d * 2 * elem;
 }
 
-void build_tables(const pk_plan& plan, int Hq, int Hkv, int d, int dtype, DeviceTables& t) {
+void build_tables(const pk_plan& plan, int Hq, int Hkv, int d, int dtype, int num_cus, DeviceTables& t) {
     t = DeviceTables();
     t.Hq = Hq; t.Hkv = Hkv; t.d = d; t.dtype = dtype;
     Builder b(t.host);
@@ -460,7 +452,7 @@ void build_tables(const pk_plan& plan, int Hq, int Hkv, int d, int dtype, Device
     t.q_start = b.add(std::vector<int32_t>(q_start.begin(), q_start.end()));
     t.kv_start = b.add(std::vector<int32_t>(kv_start.begin(), kv_start.end()));
     build_reorg(plan, b, t);
-    if (plan.decode_only) build_decode(plan, Hq, Hkv, b, t);
+    if (plan.decode_only) build_decode(plan, Hq, Hkv, num_cus, b, t);
     build_prefill_packed(plan, q_start, kv_start, b, t);
     t.host.resize((t.host.size() + 63) / 64 * 64, 0);
     t.tables_bytes = t.host.size() * sizeof(int32_t);

@@ -104,41 +104,43 @@ int check_lengths(const char* who, const int32_t* kv_lens, int32_t n) {
 extern "C" int pk_trie_partition(const int32_t* token_ids, const int32_t* kv_lens, int32_t n,
                                  int32_t min_prefix, int32_t* prefix_ids, int32_t* prefix_lens,
                                  int64_t* saved_tokens) {
-    if (n < 0 || min_prefix < 1) return fail("pk_trie_partition: n >= 0 and min_prefix >= 1 required");
-    if (n > 0 && (!token_ids || !kv_lens || !prefix_ids || !prefix_lens))
-        return fail("pk_trie_partition: NULL pointer");
-    if (check_lengths("pk_trie_partition", kv_lens, n) != PK_OK) return PK_EINVAL;
-    for (int32_t i = 0; i < n; ++i) { prefix_ids[i] = -1; prefix_lens[i] = 0; }
-    if (saved_tokens) *saved_tokens = 0;
-    if (n < 2) return PK_OK;
-    std::vector<int32_t> idx;
-    std::vector<Interval> iv;
-    lcp_intervals(token_ids, kv_lens, n, min_prefix, idx, iv);
-    struct Family { int32_t depth, first; int32_t lo, hi; };
-    std::vector<Family> fams;
-    std::vector<int32_t> walk{0};
-    while (!walk.empty()) {
-        const Interval& x = iv[static_cast<size_t>(walk.back())];
-        walk.pop_back();
-        if (x.take) {
-            int32_t first = idx[x.lo];
-            for (int32_t p = x.lo; p <= x.hi; ++p) first = std::min(first, idx[p]);
-            fams.push_back({x.depth, first, x.lo, x.hi});
-        } else {
-            for (int32_t c : x.kids) walk.push_back(c);
+    return pk::guarded<int>(PK_ENOMEM, PK_EINVAL, "pk_trie_partition", [&]() -> int {
+        if (n < 0 || min_prefix < 1) return fail("pk_trie_partition: n >= 0 and min_prefix >= 1 required");
+        if (n > 0 && (!token_ids || !kv_lens || !prefix_ids || !prefix_lens))
+            return fail("pk_trie_partition: NULL pointer");
+        if (check_lengths("pk_trie_partition", kv_lens, n) != PK_OK) return PK_EINVAL;
+        for (int32_t i = 0; i < n; ++i) { prefix_ids[i] = -1; prefix_lens[i] = 0; }
+        if (saved_tokens) *saved_tokens = 0;
+        if (n < 2) return PK_OK;
+        std::vector<int32_t> idx;
+        std::vector<Interval> iv;
+        lcp_intervals(token_ids, kv_lens, n, min_prefix, idx, iv);
+        struct Family { int32_t depth, first; int32_t lo, hi; };
+        std::vector<Family> fams;
+        std::vector<int32_t> walk{0};
+        while (!walk.empty()) {
+            const Interval& x = iv[static_cast<size_t>(walk.back())];
+            walk.pop_back();
+            if (x.take) {
+                int32_t first = idx[x.lo];
+                for (int32_t p = x.lo; p <= x.hi; ++p) first = std::min(first, idx[p]);
+                fams.push_back({x.depth, first, x.lo, x.hi});
+            } else {
+                for (int32_t c : x.kids) walk.push_back(c);
+            }
         }
-    }
-    std::sort(fams.begin(), fams.end(), [](const Family& a, const Family& b) { return a.first < b.first; });
-    int64_t saved = 0;
-    for (size_t f = 0; f < fams.size(); ++f) {
-        for (int32_t p = fams[f].lo; p <= fams[f].hi; ++p) {
-            prefix_ids[idx[p]] = static_cast<int32_t>(f);
-            prefix_lens[idx[p]] = fams[f].depth;
+        std::sort(fams.begin(), fams.end(), [](const Family& a, const Family& b) { return a.first < b.first; });
+        int64_t saved = 0;
+        for (size_t f = 0; f < fams.size(); ++f) {
+            for (int32_t p = fams[f].lo; p <= fams[f].hi; ++p) {
+                prefix_ids[idx[p]] = static_cast<int32_t>(f);
+                prefix_lens[idx[p]] = fams[f].depth;
+            }
+            saved += static_cast<int64_t>(fams[f].depth) * (fams[f].hi - fams[f].lo);
         }
-        saved += static_cast<int64_t>(fams[f].depth) * (fams[f].hi - fams[f].lo);
-    }
-    if (saved_tokens) *saved_tokens = saved;
-    return PK_OK;
+        if (saved_tokens) *saved_tokens = saved;
+        return PK_OK;
+    });
 }
 
 // The whole prefix tree as a forest of shared segments: every LCP interval of at least min_prefix
@@ -147,56 +149,58 @@ extern "C" int pk_trie_partition(const int32_t* token_ids, const int32_t* kv_len
 extern "C" int pk_trie_tree(const int32_t* token_ids, const int32_t* kv_lens, int32_t n,
                             int32_t min_prefix, int32_t* node_parent, int32_t* node_len,
                             int32_t* n_nodes, int32_t* req_node, int64_t* saved_tokens) {
-    if (n < 0 || min_prefix < 1) return fail("pk_trie_tree: n >= 0 and min_prefix >= 1 required");
-    if (!n_nodes) return fail("pk_trie_tree: n_nodes is NULL");
-    if (n > 0 && (!token_ids || !kv_lens || !node_parent || !node_len || !req_node))
-        return fail("pk_trie_tree: NULL pointer");
-    if (check_lengths("pk_trie_tree", kv_lens, n) != PK_OK) return PK_EINVAL;
-    for (int32_t i = 0; i < n; ++i) req_node[i] = -1;
-    *n_nodes = 0;
-    if (saved_tokens) *saved_tokens = 0;
-    if (n < 2) return PK_OK;
-    std::vector<int32_t> idx;
-    std::vector<Interval> iv;
-    lcp_intervals(token_ids, kv_lens, n, min_prefix, idx, iv);
+    return pk::guarded<int>(PK_ENOMEM, PK_EINVAL, "pk_trie_tree", [&]() -> int {
+        if (n < 0 || min_prefix < 1) return fail("pk_trie_tree: n >= 0 and min_prefix >= 1 required");
+        if (!n_nodes) return fail("pk_trie_tree: n_nodes is NULL");
+        if (n > 0 && (!token_ids || !kv_lens || !node_parent || !node_len || !req_node))
+            return fail("pk_trie_tree: NULL pointer");
+        if (check_lengths("pk_trie_tree", kv_lens, n) != PK_OK) return PK_EINVAL;
+        for (int32_t i = 0; i < n; ++i) req_node[i] = -1;
+        *n_nodes = 0;
+        if (saved_tokens) *saved_tokens = 0;
+        if (n < 2) return PK_OK;
+        std::vector<int32_t> idx;
+        std::vector<Interval> iv;
+        lcp_intervals(token_ids, kv_lens, n, min_prefix, idx, iv);
 
-    struct Seg { int32_t first, depth, parent_depth, lo, hi, parent_iv, number; };
-    std::vector<Seg> segs;
-    std::vector<int32_t> seg_of(iv.size(), -1);
-    // top-down: (interval, nearest ancestor that is a node)
-    std::vector<std::pair<int32_t, int32_t>> walk{{0, -1}};
-    while (!walk.empty()) {
-        const int32_t v = walk.back().first;
-        int32_t anc = walk.back().second;
-        walk.pop_back();
-        const Interval& x = iv[static_cast<size_t>(v)];
-        if (x.depth >= min_prefix) {
-            int32_t first = idx[x.lo];
-            for (int32_t p = x.lo; p <= x.hi; ++p) first = std::min(first, idx[p]);
-            const int32_t pd = anc >= 0 ? iv[static_cast<size_t>(anc)].depth : 0;
-            seg_of[static_cast<size_t>(v)] = static_cast<int32_t>(segs.size());
-            segs.push_back({first, x.depth, pd, x.lo, x.hi, anc, 0});
-            anc = v;
+        struct Seg { int32_t first, depth, parent_depth, lo, hi, parent_iv, number; };
+        std::vector<Seg> segs;
+        std::vector<int32_t> seg_of(iv.size(), -1);
+        // top-down: (interval, nearest ancestor that is a node)
+        std::vector<std::pair<int32_t, int32_t>> walk{{0, -1}};
+        while (!walk.empty()) {
+            const int32_t v = walk.back().first;
+            int32_t anc = walk.back().second;
+            walk.pop_back();
+            const Interval& x = iv[static_cast<size_t>(v)];
+            if (x.depth >= min_prefix) {
+                int32_t first = idx[x.lo];
+                for (int32_t p = x.lo; p <= x.hi; ++p) first = std::min(first, idx[p]);
+                const int32_t pd = anc >= 0 ? iv[static_cast<size_t>(anc)].depth : 0;
+                seg_of[static_cast<size_t>(v)] = static_cast<int32_t>(segs.size());
+                segs.push_back({first, x.depth, pd, x.lo, x.hi, anc, 0});
+                anc = v;
+            }
+            for (int32_t c : x.kids) walk.push_back({c, anc});
         }
-        for (int32_t c : x.kids) walk.push_back({c, anc});
-    }
-    std::vector<int32_t> order(segs.size());
-    std::iota(order.begin(), order.end(), 0);
-    std::sort(order.begin(), order.end(), [&](int32_t a, int32_t b) {
-        if (segs[a].first != segs[b].first) return segs[a].first < segs[b].first;
-        return segs[a].depth < segs[b].depth;
+        std::vector<int32_t> order(segs.size());
+        std::iota(order.begin(), order.end(), 0);
+        std::sort(order.begin(), order.end(), [&](int32_t a, int32_t b) {
+            if (segs[a].first != segs[b].first) return segs[a].first < segs[b].first;
+            return segs[a].depth < segs[b].depth;
+        });
+        for (size_t k = 0; k < order.size(); ++k) segs[static_cast<size_t>(order[k])].number = static_cast<int32_t>(k);
+        int64_t saved = 0;
+        std::vector<int32_t> deepest(static_cast<size_t>(n), 0);
+        for (const Seg& sg : segs) {
+            node_parent[sg.number] = sg.parent_iv >= 0 ? segs[static_cast<size_t>(seg_of[static_cast<size_t>(sg.parent_iv)])].number : -1;
+            node_len[sg.number] = sg.depth - sg.parent_depth;
+            saved += static_cast<int64_t>(sg.depth - sg.parent_depth) * (sg.hi - sg.lo);
+            for (int32_t p = sg.lo; p <= sg.hi; ++p)
+                if (sg.depth > deepest[idx[p]]) { deepest[idx[p]] = sg.depth; req_node[idx[p]] = sg.number; }
+        }
+        *n_nodes = static_cast<int32_t>(segs.size());
+        if (saved_tokens) *saved_tokens = saved;
+        return PK_OK;
     });
-    for (size_t k = 0; k < order.size(); ++k) segs[static_cast<size_t>(order[k])].number = static_cast<int32_t>(k);
-    int64_t saved = 0;
-    std::vector<int32_t> deepest(static_cast<size_t>(n), 0);
-    for (const Seg& sg : segs) {
-        node_parent[sg.number] = sg.parent_iv >= 0 ? segs[static_cast<size_t>(seg_of[static_cast<size_t>(sg.parent_iv)])].number : -1;
-        node_len[sg.number] = sg.depth - sg.parent_depth;
-        saved += static_cast<int64_t>(sg.depth - sg.parent_depth) * (sg.hi - sg.lo);
-        for (int32_t p = sg.lo; p <= sg.hi; ++p)
-            if (sg.depth > deepest[idx[p]]) { deepest[idx[p]] = sg.depth; req_node[idx[p]] = sg.number; }
-    }
-    *n_nodes = static_cast<int32_t>(segs.size());
-    if (saved_tokens) *saved_tokens = saved;
-    return PK_OK;
 }

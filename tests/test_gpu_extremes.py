@@ -70,3 +70,47 @@ def test_decode_family_with_many_more_members_than_a_work_item():
     pk.packed_decode_attn(plan, w.q, buf, out, w.scale, w.Hkv, ws)
     torch.cuda.synchronize()
     H.assert_close(out.cpu().numpy(), H.oracle_paged_decode(w, False), 0, "family of 150")
+
+
+@pytest.mark.parametrize("r", [3, 5, 32])
+def test_head_ratios_that_are_not_small_powers_of_two(r):
+    """The library accepts any Hq/Hkv up to 32 on the bf16 decode path and any ratio on the prefill
+    path: ratios that do not divide the 16- and 32-row work items, and the largest one."""
+    Hkv = 2
+    w = wl.small_paged(seed=40 + r, n=14, lo=1, hi=260, Hq=Hkv * r, Hkv=Hkv, d=128, token_budget=900,
+                       families=2, prefix_lo=20, prefix_hi=150, device=DEV, keep_f32=False)
+    ones = np.ones(w.n, dtype=np.int32)
+    plan = pk.pack_plan(w.kv_lens, ones, w.prefix_ids, w.prefix_lens, w.token_budget, 0)
+    ws = pk.new_workspace(plan, w.Hq, w.Hkv, w.d, pk.PK_BF16)
+    buf = pk.new_kv_buf(plan, w.Hkv, w.d, pk.PK_BF16, fill=0x7F)
+    pk.kv_reorganize(plan, w.k_pages, w.v_pages, torch.from_numpy(w.block_table).to(DEV), buf, ws)
+    out = torch.full(w.q.shape, float("nan"), dtype=torch.float32, device=DEV)
+    pk.packed_decode_attn(plan, w.q, buf, out, w.scale, w.Hkv, ws)
+    torch.cuda.synchronize()
+    H.assert_close(out.cpu().numpy(), H.oracle_paged_decode(w, False), 0, f"decode Hq/Hkv = {r}")
+    p = wl.small_ragged(seed=50 + r, n=4, lo=5, hi=200, Hq=Hkv * r, Hkv=Hkv, d=128, token_budget=300,
+                        device=DEV, ctx_hi=90, keep_f32=False)
+    plan = pk.pack_plan(p.kv_lens, p.q_lens, token_budget=p.token_budget)
+    ws = pk.new_workspace(plan, p.Hq, p.Hkv, p.d, pk.PK_BF16)
+    out = torch.full(p.q.shape, float("nan"), dtype=torch.float32, device=DEV)
+    pk.packed_prefill_attn(plan, p.q, p.k, p.v, out, p.scale, ws)
+    torch.cuda.synchronize()
+    H.assert_close(out.cpu().numpy(), H.oracle_ragged(p, False), 0, f"prefill Hq/Hkv = {r}")
+
+
+def test_two_plans_taking_turns_on_one_workspace():
+    """A workspace belongs to the plan that bound it last: two plans that alternate on one
+    workspace through the compute calls alone (no explicit bind) each get their own tables."""
+    a = wl.small_ragged(seed=71, n=5, lo=10, hi=260, Hq=4, Hkv=2, d=128, token_budget=300, device=DEV, keep_f32=False)
+    b = wl.small_ragged(seed=72, n=9, lo=1, hi=90, Hq=4, Hkv=2, d=128, token_budget=200, device=DEV, keep_f32=False)
+    pa = pk.pack_plan(a.kv_lens, a.q_lens, token_budget=a.token_budget)
+    pb = pk.pack_plan(b.kv_lens, b.q_lens, token_budget=b.token_budget)
+    nbytes = max(pa.workspace_bytes(4, 2, 128, pk.PK_BF16), pb.workspace_bytes(4, 2, 128, pk.PK_BF16))
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+    want_a, want_b = H.oracle_ragged(a, False), H.oracle_ragged(b, False)
+    for turn in range(3):
+        for w, plan, want in ((a, pa, want_a), (b, pb, want_b)):
+            out = torch.full(w.q.shape, float("nan"), dtype=torch.float32, device=DEV)
+            pk.packed_prefill_attn(plan, w.q, w.k, w.v, out, w.scale, ws)
+            torch.cuda.synchronize()
+            H.assert_close(out.cpu().numpy(), want, 0, f"turn {turn} {w.name}")

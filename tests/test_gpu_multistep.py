@@ -128,9 +128,9 @@ def test_grown_zero_equals_plain_decode():
     assert torch.equal(a, b)
 
 
-def test_config3_full_size_32_steps_sampled():
+def test_config3_full_size_32_steps_all_requests():
     """Configuration 3 at full size with the 32 slots of headroom bench.py uses: 32 appended tokens
-    per request, attention after the first and after the last step on sampled requests."""
+    per request, attention after the first, a middle and the last step, every request and head."""
     w = wl.config3(0, device=DEV)
     steps = 32
     ones = np.ones(w.n, dtype=np.int32)
@@ -138,8 +138,7 @@ def test_config3_full_size_32_steps_sampled():
     ws = pk.new_workspace(plan, w.Hq, w.Hkv, w.d, pk.PK_BF16)
     kv_buf = pk.new_kv_buf(plan, w.Hkv, w.d, pk.PK_BF16)
     pk.kv_reorganize(plan, w.k_pages, w.v_pages, torch.from_numpy(w.block_table).to(DEV), kv_buf, ws)
-    order = np.argsort(w.kv_lens)
-    reqs = sorted({int(order[0]), int(order[-1]), int(order[len(order) // 2]), 7, 100, 201})
+    reqs = list(range(w.n))
     base_kv = {i: logical(w, False, i) for i in reqs}
     gen = torch.Generator(device=DEV).manual_seed(17)
     app_k, app_v = [], []
@@ -149,7 +148,7 @@ def test_config3_full_size_32_steps_sampled():
         app_k.append(k_new[reqs].float().cpu().numpy())
         app_v.append(v_new[reqs].float().cpu().numpy())
         pk.kv_append(plan, k_new, v_new, kv_buf, step, ws)
-        if step not in (0, steps - 1):
+        if step not in (0, steps // 2, steps - 1):
             continue
         q_step = torch.randn(w.q.shape, generator=gen, device=DEV).to(torch.bfloat16)
         out = torch.full(w.q.shape, float("nan"), dtype=torch.float32, device=DEV)

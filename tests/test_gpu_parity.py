@@ -179,87 +179,80 @@ def test_empty_batch_is_a_no_op():
 
 
 # ------------------------------------------------- benchmark configurations at full size
-def _sample_requests(lens, rng, k=6):
-    """A few requests covering the extremes and the middle of the length mix."""
-    order = np.argsort(lens)
-    pick = {int(order[0]), int(order[-1]), int(order[len(order) // 2])}
-    pick.update(int(x) for x in rng.choice(len(lens), size=min(k, len(lens)), replace=False))
-    return sorted(pick)
-
-
-@pytest.mark.parametrize("cfg", ["cfg3", "cfg4"])
-def test_decode_configs_full_size(cfg):
-    """Configurations 3 and 4 at full size, in the launch configuration bench.py times;
-    every request is checked for 3/4 (the oracle needs a few seconds)."""
-    w = wl.config3(0, device=DEV) if cfg == "cfg3" else wl.config4(0, device=DEV)
+def _decode_all_requests(w, what):
+    """Packed and padded decode of a paged workload at full size, EVERY request and head against the oracle."""
     got, plan, _ = run_decode(w, False, out_f32=False)
-    rng = np.random.default_rng(0)
-    reqs = _sample_requests(w.kv_lens, rng, k=24)
-    want = H.oracle_paged_decode(w, False, reqs)
-    H.assert_close(got[reqs], want, 0, f"{cfg} packed decode")
+    want = H.oracle_paged_decode(w, False)
+    H.assert_close(got, want, 0, f"{what} packed decode")
     ws = pk.new_workspace(plan, w.Hq, w.Hkv, w.d, pk.PK_BF16)
     out = torch.full(w.q.shape, float("nan"), dtype=torch.bfloat16, device=DEV)
     pk.padded_decode_attn(plan, w.q, w.k_pages, w.v_pages, torch.from_numpy(w.block_table).to(DEV), out, w.scale, ws)
     torch.cuda.synchronize()
-    H.assert_close(out.float().cpu().numpy()[reqs], want, 0, f"{cfg} padded decode")
-    assert np.all(np.isfinite(got))
+    H.assert_close(out.float().cpu().numpy(), want, 0, f"{what} padded decode")
+    return plan
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+@pytest.mark.parametrize("cfg", ["cfg3", "cfg4"])
+def test_decode_configs_full_size(cfg, seed):
+    """Configurations 3 and 4 at full size, in the launch configuration bench.py times: all
+    requests and all heads are compared with the oracle, packed and padded."""
+    w = wl.config3(seed, device=DEV) if cfg == "cfg3" else wl.config4(seed, device=DEV)
+    plan = _decode_all_requests(w, f"{cfg} seed {seed}")
     if cfg == "cfg4":                                      # families co-located, prefix stored once
         assert plan.unique_tokens < int(w.kv_lens.sum()) // 4
 
 
-def test_config2_prefill_full_size_sampled_rows():
-    """Configuration 2 at full size: sampled (request, head, row) outputs against the oracle,
-    plus properties that hold for every row."""
-    w = wl.config2(0, device=DEV)
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_config2_prefill_full_size_every_row(seed):
+    """Configuration 2 at full size: every output row of every head against the oracle, for the
+    packed and the padded schedule."""
+    w = wl.config2(seed, device=DEV)
+    want = H.oracle_ragged(w, False)
     got, plan = run_prefill(w, False, out_f32=False)
-    rng = np.random.default_rng(1)
-    rows = []
-    for i in _sample_requests(w.q_lens, rng, k=10):
-        L = int(w.q_lens[i])
-        for t in sorted({0, L - 1, L // 2, int(rng.integers(0, L)), int(rng.integers(0, L))}):
-            for h in (0, 5, 31):
-                rows.append((i, h, t))
-    want = H.oracle_ragged(w, False, rows=rows)
-    qs = w.q_start
-    sel = np.stack([got[qs[i] + t, h] for (i, h, t) in rows])
-    H.assert_close(sel, want, 0, "cfg2 sampled rows")
-    assert np.all(np.isfinite(got))
+    H.assert_close(got, want, 0, f"cfg2 seed {seed} packed, all rows")
+    got_pad, _ = run_prefill(w, False, padded=True, out_f32=False)
+    H.assert_close(got_pad, want, 0, f"cfg2 seed {seed} padded, all rows")
     # first causal row of every request returns v[0] of its KV head (up to bf16 rounding of the output)
     v = w.v.float().cpu().numpy()
-    ks = w.kv_start
+    qs, ks = w.q_start, w.kv_start
     for i in range(w.n):
         assert np.max(np.abs(got[qs[i], 7] - v[ks[i], 7 // 4])) <= 2e-2
-    got_pad, _ = run_prefill(w, False, padded=True, out_f32=False)
-    selp = np.stack([got_pad[qs[i] + t, h] for (i, h, t) in rows])
-    H.assert_close(selp, want, 0, "cfg2 padded sampled rows")
 
 
-def test_config5_mixed_step_sampled():
-    """Configuration 5 (70B shape, chunked prefill with context + long decode rows), reduced
-    request counts so that the pool fits quickly; same per-request shapes and length mix."""
+def test_config5_mixed_step_reduced():
+    """Configuration 5 (70B shape, chunked prefill with context + long decode rows) with fewer
+    requests of the same shapes and length mix: every 4th prefill row (heads in rotation) and every
+    decode request."""
     w = wl.config5(0, device=DEV, chunks=6, decodes=48)
     got, plan = run_prefill(w.prefill, False, out_f32=False)
-    rng = np.random.default_rng(2)
-    rows = []
-    for i in range(w.prefill.n):
-        L = int(w.prefill.q_lens[i])
-        for t in (0, L - 1, int(rng.integers(0, L))):
-            rows.append((i, int(rng.integers(0, 64)), t))
+    rows = _strided_rows(w.prefill, 4)
     want = H.oracle_ragged(w.prefill, False, rows=rows)
     qs = w.prefill.q_start
     sel = np.stack([got[qs[i] + t, h] for (i, h, t) in rows])
-    H.assert_close(sel, want, 0, "cfg5 prefill sampled rows")
-    d = w.decode
-    gotd, pland, _ = run_decode(d, False, out_f32=False)
-    reqs = _sample_requests(d.kv_lens, rng, k=8)
-    wantd = H.oracle_paged_decode(d, False, reqs)
-    H.assert_close(gotd[reqs], wantd, 0, "cfg5 decode")
-    assert np.all(np.isfinite(gotd))
+    H.assert_close(sel, want, 0, "cfg5 reduced prefill")
+    assert np.all(np.isfinite(got))
+    _decode_all_requests(w.decode, "cfg5 reduced")
 
 
-def test_config5_full_size_sampled():
+def _strided_rows(p, stride):
+    """(request, head, row) triples: every `stride`-th row of every request plus its last row,
+    heads in rotation over the triples; with stride <= 16 every 32-row wave slice of every query
+    tile holds at least one of them, however the schedule cuts the tiles."""
+    rows, c = [], 0
+    for i in range(p.n):
+        L = int(p.q_lens[i])
+        for t in sorted(set(range(0, L, stride)) | {L - 1}):
+            rows.append((i, c % p.Hq, t))
+            c += 1
+    return rows
+
+
+def test_config5_full_size():
     """Configuration 5 at the size bench.py runs (32 chunks with context, 480 decode requests,
-    17.7 GB of K/V): sampled prefill rows and sampled decode requests against the oracle."""
+    17.7 GB of K/V).  Prefill: every 16th row of every chunk (at least one row in every wave of
+    every query tile; heads in rotation) and all 64 heads for a handful of rows.  Decode: all 480
+    requests, all heads."""
     w = wl.config5(0, device=DEV)
     p = w.prefill
     plan = pk.pack_plan(p.kv_lens, p.q_lens, token_budget=p.token_budget)
@@ -267,19 +260,25 @@ def test_config5_full_size_sampled():
     out = torch.full(p.q.shape, float("nan"), dtype=torch.bfloat16, device=DEV)
     pk.packed_prefill_attn(plan, p.q, p.k, p.v, out, p.scale, ws)
     torch.cuda.synchronize()
+    assert bool(torch.isfinite(out.float()).all())
+    rows = _strided_rows(p, 16)
     rng = np.random.default_rng(3)
-    rows = []
-    for i in _sample_requests(p.q_lens, rng, k=5):
-        L = int(p.q_lens[i])
-        for t in (0, L - 1, int(rng.integers(0, L))):
-            rows.append((int(i), int(rng.integers(0, p.Hq)), t))
+    for i in rng.choice(p.n, size=4, replace=False):
+        t = int(rng.integers(0, int(p.q_lens[i])))
+        rows += [(int(i), h, t) for h in range(p.Hq)]
     qs = p.q_start
     idx = torch.tensor([qs[i] + t for (i, h, t) in rows], device=DEV)
     hh = torch.tensor([h for (i, h, t) in rows], device=DEV)
     sel = out[idx, hh].float().cpu().numpy()
-    assert bool(torch.isfinite(out.float()).all())
-    H.assert_close(sel, H.oracle_ragged(p, False, rows=rows), 0, "cfg5 full prefill sampled rows")
+    H.assert_close(sel, H.oracle_ragged(p, False, rows=rows), 0, "cfg5 full prefill")
+    # the padded schedule on the same rows
+    out.fill_(float("nan"))
+    pk.padded_prefill_attn(plan, p.q, p.k, p.v, out, p.scale, ws)
+    torch.cuda.synchronize()
+    H.assert_close(out[idx, hh].float().cpu().numpy(), H.oracle_ragged(p, False, rows=rows), 0, "cfg5 full padded prefill")
     del out, ws, plan
+    w.prefill = None
+    torch.cuda.empty_cache()
     d = w.decode
     ones = np.ones_like(d.kv_lens)
     pland = pk.pack_plan(d.kv_lens, ones, d.prefix_ids, d.prefix_lens, d.token_budget, 0)
@@ -290,7 +289,4 @@ def test_config5_full_size_sampled():
     outd = torch.full(d.q.shape, float("nan"), dtype=torch.float32, device=DEV)
     pk.packed_decode_attn(pland, d.q, buf, outd, d.scale, d.Hkv, wsd)
     torch.cuda.synchronize()
-    assert bool(torch.isfinite(outd).all())
-    reqs = _sample_requests(d.kv_lens, rng, k=6)
-    H.assert_close(outd[torch.as_tensor(np.asarray(reqs), device=DEV)].cpu().numpy(),
-                   H.oracle_paged_decode(d, False, reqs), 0, "cfg5 full decode")
+    H.assert_close(outd.cpu().numpy(), H.oracle_paged_decode(d, False), 0, "cfg5 full decode, all requests")

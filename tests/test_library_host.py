@@ -332,3 +332,31 @@ def test_parsed_groups_of_a_tree_plan():
     assert sum(nd[2] for nd in nodes) + sum(m[3] for m in members) == plan.unique_tokens
     flat = pk.pack_plan([10, 20], None, None, None, 64, 0).groups()
     assert flat[0]["nodes"] == [] and len(flat[0]["members"][0]) == 5
+
+
+def test_tiny_budget_does_not_blow_up_the_group_table():
+    # ceil(L_total / C) groups would be one per token at C = 1; the planner caps the table at the
+    # number of items and still gives the oracle's words (empty groups are dropped either way)
+    kv = [50000, 3, 70000, 1]
+    for C in (1, 2, 7):
+        plan = pk.pack_plan(kv, None, None, None, C, 0)
+        assert np.array_equal(plan.words(), oracle_words(kv, None, None, None, C, 0))
+        assert plan.num_groups == 4
+
+
+def test_tune_decode_split_changes_only_the_schedule():
+    kv = wl.config3_lengths(0)
+    plan = pk.pack_plan(kv, np.ones_like(kv), None, None, 16384)
+    plan.workspace_bytes(32, 8, 128, pk.PK_BF16)
+    auto_split, auto_items = plan.stat(5), plan.stat(3)
+    words = plan.words().copy()
+    plan.tune(pk.TUNE_DECODE_SPLIT, 256)
+    plan.workspace_bytes(32, 8, 128, pk.PK_BF16)
+    assert plan.stat(5) == 256 and plan.stat(3) > auto_items
+    plan.tune(pk.TUNE_DECODE_SPLIT, 0)
+    plan.workspace_bytes(32, 8, 128, pk.PK_BF16)
+    assert plan.stat(5) == auto_split and plan.stat(3) == auto_items
+    assert np.array_equal(plan.words(), words)
+    L = pk.lib()
+    assert L.pk_plan_tune(plan.handle, 99, 1) == -1 and L.pk_plan_tune(plan.handle, 0, -5) == -1
+    assert L.pk_plan_tune(None, 0, 0) == -1
