@@ -238,6 +238,31 @@ int pk_packed_decode_attn(pk_plan* plan, const void* q, const void* kv_buf,
                           int dtype, int out_dtype,
                           void* workspace, size_t workspace_bytes, void* stream);
 
+/* pk_packed_decode_attn_static -- pk_packed_decode_attn for callers that
+ * cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  It takes no workspace: the plan's
+ * device tables and the split-KV partial results live in a fixed array of
+ * PK_STATIC_SCRATCH_BYTES that is part of the library's code object (every
+ * GPU the library runs on holds its own copy until the process ends).  The
+ * call allocates and frees nothing, on the device or through the runtime.
+ *   - The first call of a plan on a device (and the first after another plan
+ *     used the scratch) uploads the plan's tables with one host-to-device copy
+ *     on `stream`; further calls of that plan only launch kernels.
+ *   - A plan whose tables and partial results need more than
+ *     PK_STATIC_SCRATCH_BYTES is rejected with PK_EUNSUPPORTED and a message
+ *     that states both sizes (use pk_packed_decode_attn with a workspace).
+ *   - All calls on one GPU share the one array, which keeps the contents of
+ *     the last call: calls that overlap in time on one GPU (different
+ *     streams, different threads) race and must be ordered by the caller.
+ *     Nothing in it has to start at zero: every partial slot is written
+ *     before the merge reads it.
+ * Other arguments, results and errors as pk_packed_decode_attn; the outputs
+ * are bit-identical to that call's. */
+#define PK_STATIC_SCRATCH_BYTES (16u << 20)
+int pk_packed_decode_attn_static(pk_plan* plan, const void* q, const void* kv_buf,
+                                 void* out, float scale, int Hq, int Hkv, int d,
+                                 int dtype, int out_dtype, void* stream);
+
 /* ------------------------------------------------------------------------
  * pk_trie_partition -- TriePartition of Alg. 1 Part 2 from token ids (Sec.
  * 3.2: the requests of a batch form a prefix tree whose common prefixes are

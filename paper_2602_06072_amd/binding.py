@@ -64,6 +64,8 @@ def lib():
         getattr(L, name).argtypes = [vp, vp, vp, vp, vp, f32, ci, ci, ci, ci, ci, vp, sz, vp]
     L.pk_packed_decode_attn.restype = ci
     L.pk_packed_decode_attn.argtypes = [vp, vp, vp, vp, f32, ci, ci, ci, ci, ci, vp, sz, vp]
+    L.pk_packed_decode_attn_static.restype = ci
+    L.pk_packed_decode_attn_static.argtypes = [vp, vp, vp, vp, f32, ci, ci, ci, ci, ci, vp]
     L.pk_padded_decode_attn.restype = ci
     L.pk_padded_decode_attn.argtypes = [vp, vp, vp, vp, vp, i32, i32, i64, vp, f32, ci, ci, ci, ci, ci, vp, sz, vp]
     L.pk_packed_decode_attn_grown.restype = ci
@@ -95,8 +97,9 @@ EXPORTS = [
     "pk_kv_reorganize", "pk_packed_prefill_attn", "pk_packed_decode_attn",
     "pk_padded_prefill_attn", "pk_padded_decode_attn", "pk_plan_stat", "pk_last_error",
     "pk_kv_append", "pk_packed_decode_attn_grown", "pk_regroup_due", "pk_trie_partition",
-    "pk_pack_plan_tree", "pk_trie_tree", "pk_plan_tune",
+    "pk_pack_plan_tree", "pk_trie_tree", "pk_plan_tune", "pk_packed_decode_attn_static",
 ]
+STATIC_SCRATCH_BYTES = 16 << 20
 TUNE_DECODE_SPLIT = 0
 REGROUP_DRIFT, REGROUP_HEADROOM, REGROUP_DRIFT_WITHIN_BUDGET = 1, 2, 4
 
@@ -299,6 +302,18 @@ def packed_decode_attn(plan, q, kv_buf, out, scale, Hkv, workspace, stream=None)
         workspace.numel() * workspace.element_size(), _stream(stream))
     _check(rc, "pk_packed_decode_attn")
     plan._ws = workspace
+    return out
+
+
+def packed_decode_attn_static(plan, q, kv_buf, out, scale, Hkv, stream=None):
+    """packed_decode_attn without a workspace: tables and partial results live in the library's
+    fixed scratch array (for callers that cannot allocate device memory)."""
+    n, Hq, d = q.shape
+    rc = lib().pk_packed_decode_attn_static(
+        plan.handle, _ptr(q), _ptr(kv_buf), _ptr(out), float(scale), Hq, Hkv, d,
+        _dtype_code(q), _dtype_code(out), _stream(stream))
+    _check(rc, "pk_packed_decode_attn_static")
+    plan._ws = None
     return out
 
 

@@ -51,11 +51,12 @@ struct Staging {
 std::mutex g_staging_mutex;
 std::vector<Staging> g_staging;
 
-Staging* staging_acquire(size_t bytes) {
+// may_allocate = false: only a buffer that already exists is handed out
+Staging* staging_acquire(size_t bytes, bool may_allocate) {
     std::lock_guard<std::mutex> lock(g_staging_mutex);
     for (Staging& s : g_staging)
         if (!s.busy && s.cap >= bytes && (!s.used || hipEventQuery(s.done) == hipSuccess)) { s.busy = true; return &s; }
-    if (g_staging.size() >= 64) return nullptr;     // fall back to a pageable copy
+    if (!may_allocate || g_staging.size() >= 64) return nullptr;     // fall back to a pageable copy
     Staging s;
     s.cap = (bytes + (1u << 20) - 1) >> 20 << 20;
     if (hipHostMalloc(&s.ptr, s.cap, hipHostMallocDefault) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
@@ -75,9 +76,9 @@ void staging_release(Staging* s, bool recorded) {
     s->busy = false;
 }
 
-int copy_tables(void* dst, const void* src, size_t bytes, void* stream) {
+int copy_tables(void* dst, const void* src, size_t bytes, void* stream, bool may_allocate = true) {
     hipStream_t st = static_cast<hipStream_t>(stream);
-    Staging* s = staging_acquire(bytes);
+    Staging* s = staging_acquire(bytes, may_allocate);
     if (!s) return static_cast<int>(hipMemcpyAsync(dst, src, bytes, hipMemcpyHostToDevice, st));
     std::memcpy(s->ptr, src, bytes);
     hipError_t e = hipMemcpyAsync(dst, s->ptr, bytes, hipMemcpyHostToDevice, st);
@@ -126,8 +127,10 @@ int device_cus() {
 }
 
 // Makes sure the plan's device tables for this shape live in `workspace`.
+// fixed_scratch: `workspace` is the library's own fixed array (pk_packed_decode_attn_static): it
+// only has to hold the tables and the packed decode partials, and nothing may be allocated.
 int ensure_bound(pk_plan* plan, int Hq, int Hkv, int d, int dtype, void* workspace,
-                 size_t workspace_bytes, void* stream) {
+                 size_t workspace_bytes, void* stream, bool fixed_scratch = false) {
     DeviceTables& t = plan->tables;
     const bool same_shape = t.Hq == Hq && t.Hkv == Hkv && t.d == d && t.dtype == dtype;
     if (same_shape && plan->bound_ws == workspace && plan->bound_bytes == workspace_bytes &&
@@ -135,9 +138,16 @@ int ensure_bound(pk_plan* plan, int Hq, int Hkv, int d, int dtype, void* workspa
     if (!workspace) return fail(PK_EINVAL, "workspace is NULL");
     if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0) return fail(PK_EINVAL, "workspace must be 256-byte aligned");
     if (!same_shape) build_tables(*plan, Hq, Hkv, d, dtype, device_cus(), t);
-    if (workspace_bytes < t.total_bytes) return fail(PK_EINVAL, "workspace smaller than pk_workspace_bytes");
+    if (fixed_scratch) {
+        if (workspace_bytes < t.decode_only_bytes)
+            return fail(PK_EUNSUPPORTED, "pk_packed_decode_attn_static: the plan needs " + std::to_string(t.decode_only_bytes) +
+                        " bytes of tables and partial results, the fixed scratch holds " + std::to_string(workspace_bytes) +
+                        " (PK_STATIC_SCRATCH_BYTES); use pk_packed_decode_attn with a workspace");
+    } else if (workspace_bytes < t.total_bytes) {
+        return fail(PK_EINVAL, "workspace smaller than pk_workspace_bytes");
+    }
     if (t.tables_bytes) {
-        const int e = copy_tables(workspace, t.host.data(), t.tables_bytes, stream);
+        const int e = copy_tables(workspace, t.host.data(), t.tables_bytes, stream, !fixed_scratch);
         if (e != 0) return hip_fail("pk_plan_bind (copy of tables)", e);
     }
     plan->bound_ws = workspace;
@@ -292,7 +302,7 @@ namespace {
 int decode_common(const char* who, pk_plan* plan, const void* q, const void* kv_buf,
                   void* out, float scale, int32_t grown, int Hq, int Hkv, int d,
                   int dtype, int out_dtype,
-                  void* workspace, size_t workspace_bytes, void* stream) {
+                  void* workspace, size_t workspace_bytes, void* stream, bool fixed_scratch = false) {
     const std::string w(who);
     std::string why;
     if (!plan) return fail(PK_EINVAL, w + ": plan is NULL");
@@ -307,7 +317,12 @@ int decode_common(const char* who, pk_plan* plan, const void* q, const void* kv_
     if (dtype == PK_BF16 && (d != 64 && d != 128)) return fail(PK_EUNSUPPORTED, w + ": bf16 path needs d in {64,128}");
     if (dtype == PK_BF16 && Hq / Hkv > 32) return fail(PK_EUNSUPPORTED, w + ": bf16 path needs Hq/Hkv <= 32");
     if (dtype == PK_F32 && d > 256) return fail(PK_EUNSUPPORTED, w + ": fp32 path needs d <= 256");
-    int rc = ensure_bound(plan, Hq, Hkv, d, dtype, workspace, workspace_bytes, stream);
+    if (fixed_scratch) {                            // after the argument checks: the look-up touches the device
+        const int e = static_scratch_address(&workspace);
+        if (e != 0) return hip_fail("pk_packed_decode_attn_static (address of the fixed scratch)", e);
+        workspace_bytes = PK_STATIC_SCRATCH_BYTES;
+    }
+    int rc = ensure_bound(plan, Hq, Hkv, d, dtype, workspace, workspace_bytes, stream, fixed_scratch);
     if (rc != PK_OK) return rc;
     const DeviceTables& t = plan->tables;
     DecodeArgs a{};
@@ -336,6 +351,15 @@ extern "C" int pk_packed_decode_attn(pk_plan* plan, const void* q, const void* k
     return pk::guarded<int>(PK_ENOMEM, PK_EINVAL, "pk_packed_decode_attn", [&]() -> int {
         return decode_common("pk_packed_decode_attn", plan, q, kv_buf, out, scale, 0, Hq, Hkv, d, dtype, out_dtype,
                              workspace, workspace_bytes, stream);
+    });
+}
+
+extern "C" int pk_packed_decode_attn_static(pk_plan* plan, const void* q, const void* kv_buf,
+                                            void* out, float scale, int Hq, int Hkv, int d,
+                                            int dtype, int out_dtype, void* stream) {
+    return pk::guarded<int>(PK_ENOMEM, PK_EINVAL, "pk_packed_decode_attn_static", [&]() -> int {
+        return decode_common("pk_packed_decode_attn_static", plan, q, kv_buf, out, scale, 0, Hq, Hkv, d, dtype, out_dtype,
+                             nullptr, 0, stream, true);
     });
 }
 

@@ -10,6 +10,9 @@
 // MFMAs, the buffer tiles are already in MFMA operand order, so every load is
 // a fully coalesced 16-byte-per-lane read straight into the operand
 // registers (no LDS).  HBM-bound: 4*D bytes per token and KV head.
+#include <mutex>
+
+#include "../../include/packinfer.h"
 #include "common.hip.h"
 #include "kernels.h"
 
@@ -270,6 +273,31 @@ int launch_d(const DecodeArgs& a, hipStream_t st) {
 }
 
 }  // namespace
+
+// Scratch of pk_packed_decode_attn_static (plan tables + split-KV partials) for callers that
+// cannot allocate.  In host code the array's name is only a handle for hipGetSymbolAddress: the
+// device address differs per GPU and is looked up once per device, with that device current.
+static __device__ __align__(256) unsigned char scratch[PK_STATIC_SCRATCH_BYTES];
+
+int static_scratch_address(void** ptr) {
+    constexpr int kMaxDevices = 64;
+    static std::mutex mutex;
+    static void* address[kMaxDevices] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return static_cast<int>(e);
+    if (dev < 0 || dev >= kMaxDevices) return static_cast<int>(hipErrorInvalidDevice);
+    std::lock_guard<std::mutex> lock(mutex);
+    if (!address[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return static_cast<int>(e);
+        if (!p) return static_cast<int>(hipErrorInvalidSymbol);
+        address[dev] = p;
+    }
+    *ptr = address[dev];
+    return 0;
+}
 
 int launch_decode_bf16(const DecodeArgs& a, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);

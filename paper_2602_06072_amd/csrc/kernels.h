@@ -37,6 +37,9 @@ struct DecodeArgs {
     int32_t max_parts;                              // most partial results of one request
 };
 int launch_decode_bf16(const DecodeArgs& a, void* stream);
+// Device address of the library's fixed scratch array on the current device (looked up once per
+// device); returns a hipError_t as int.
+int static_scratch_address(void** ptr);
 int launch_decode_f32(const DecodeArgs& a, void* stream);
 
 struct PrefillArgs {

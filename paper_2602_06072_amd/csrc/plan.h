@@ -86,6 +86,7 @@ struct DeviceTables {
     size_t partial_offset = 0;      // bytes
     size_t partial_bytes = 0;
     size_t total_bytes = 0;
+    size_t decode_only_bytes = 0;   // tables + the packed decode partials alone (what the static scratch must hold)
 };
 
 }  // namespace pk

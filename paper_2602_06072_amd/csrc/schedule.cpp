@@ -458,6 +458,7 @@ void build_tables(const pk_plan& plan, int Hq, int Hkv, int d, int dtype, int nu
     t.tables_bytes = t.host.size() * sizeof(int32_t);
     t.partial_offset = t.tables_bytes;
     t.partial_bytes = static_cast<size_t>(t.n_dec_parts) * Hq * (static_cast<size_t>(d) + 1) * sizeof(float);
+    t.decode_only_bytes = t.partial_offset + t.partial_bytes;
     if (plan.decode_only) {
         // the padded comparison kernel keeps (request, split) partials in the same region: at most
         // 16 splits, each a multiple of 32 tokens and at least 256 tokens long
