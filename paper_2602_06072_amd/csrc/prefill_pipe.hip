@@ -100,14 +100,25 @@ __device__ __forceinline__ bool setup(const PrefillArgs& a, WorkUnit& u, LaneOff
         const int row = 16 * u.wave + 4 * q + r_in;
         off.g[q] = static_cast<int>(row * u.row_bytes + u.kvh * ROWB + ((pos ^ swz(row)) << 4));
     }
-    // Q operand: lane (n, hlf) holds Q[row n][16s + 8hlf .. +8]
+    // Q operand: lane (n, hlf) holds Q[row n][16s + 8hlf .. +8], multiplied by scale * log2(e) in
+    // fp32 and rounded to bf16 again: the MFMAs then deliver the scores in the exp2 domain and the
+    // softmax needs no multiplication per score.
     const uint16_t* qp = static_cast<const uint16_t*>(a.q) +
                          (static_cast<int64_t>(u.qrow < 0 ? 0 : u.qrow) * a.Hq + u.head) * D + 8 * u.hlf;
+    const float sl2 = a.scale * kLog2e;
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
         u32x4 raw = {0u, 0u, 0u, 0u};
         if (u.qrow >= 0) raw = *reinterpret_cast<const u32x4*>(qp + 16 * s);
-        qf[s] = __builtin_bit_cast(bf16x8, raw);
+        u32x4 scaled;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            floatx2 f;
+            f[0] = __uint_as_float(raw[w] << 16) * sl2;
+            f[1] = __uint_as_float(raw[w] & 0xFFFF0000u) * sl2;
+            scaled[w] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
+        }
+        qf[s] = __builtin_bit_cast(bf16x8, scaled);
     }
     return true;
 }
@@ -171,32 +182,39 @@ __device__ __forceinline__ void store_output_bf16(const PrefillArgs& a, const Wo
     }
 }
 
-// Copies the tile that starts at key row KSTART of `src` (a.k or a.v) into the LDS stage at byte
-// offset DST: four 1-KiB wave instructions per wave, each lane fetching the chunk that belongs at
-// its (swizzled) LDS position; rows past the end of the array arrive as zeros (the descriptor's
-// size is what is left of the array).  The copy is issued from inline assembly on purpose: the
-// compiler makes every later LDS read wait for all copies it knows of, also those into another
-// stage, which would serialise the pipeline.  The waits are explicit instead (vmcnt before the
-// barrier that publishes a stage).  The compiler does not look into the assembly for hazards: a
-// descriptor word that a VALU instruction (v_readfirstlane) wrote just before needs five wait
-// states before a memory instruction may read it, hence the s_nop 4 (it also covers M0).
+// Copies of K/V tiles into LDS stages.  A tile is 16 instructions of 1 KiB (four per wave), each
+// lane fetching the 16-byte chunk that belongs at its (swizzled) LDS position; rows past the end
+// of the array arrive as zeros (the descriptor's size is what is left of the array; a tile past
+// the end of the key-tile list gets size 0: zeros, no memory traffic).  The copy is issued from
+// inline assembly on purpose: the compiler makes every later LDS read wait for all copies it
+// knows of, also those into another stage, which would serialise the pipeline.  The waits are
+// explicit instead (vmcnt before the barrier that publishes a stage).  Descriptor and LDS address
+// are built from wave-uniform values on the scalar ALU; the compiler does not look into the
+// assembly for hazards, so the statement carries its own wait states: one is what a scalar write
+// of M0 needs, five would cover a descriptor word written by a vector instruction.
 __device__ __forceinline__ void lds_copy_16(const u32x4& rsrc, uint32_t lds_addr, int voffset) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 4\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
-                 :: "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(voffset), "s"(rsrc)
+                 :: "s"(lds_addr), "v"(voffset), "s"(rsrc)
                  : "memory");                       // M0 has no other user in this file
 }
-#define PK_COPY_TILE(SRC, KSTART, DST)                                                       \
+// descriptor of the tile that starts at key row KSTART of SRC (a.k or a.v); ENABLED = false: empty
+#define PK_TILE_DESC(RS, SRC, KSTART, ENABLED)                                               \
+    u32x4 RS;                                                                                \
     {                                                                                        \
         const uint32_t ks_ = static_cast<uint32_t>(KSTART);       /* row counts fit 31 bits */ \
         const uint64_t base_ = reinterpret_cast<uint64_t>(SRC) + static_cast<uint64_t>(ks_) * u.row_bytes32; \
         const uint64_t left_ = static_cast<uint64_t>(u.total_rows32 - ks_) * u.row_bytes32;  \
-        u32x4 rs_;                                /* wave-uniform by construction: keep it in SGPRs */ \
-        rs_[0] = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(base_));               \
-        rs_[1] = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(base_ >> 32) & 0xFFFFu);  /* stride 0: raw buffer */ \
-        rs_[2] = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(left_ > 0x7FFFFFFFull ? 0x7FFFFFFFull : left_)); \
-        rs_[3] = 0x00020000u;                                                                \
-        _Pragma("unroll") for (int q = 0; q < 4; ++q)                                        \
-            lds_copy_16(rs_, lds_base + (DST) + u.wave * 4096 + q * 1024, off.g[q]);         \
+        RS[0] = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(base_));               \
+        RS[1] = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(base_ >> 32) & 0xFFFFu);  /* stride 0: raw buffer */ \
+        RS[2] = __builtin_amdgcn_readfirstlane((ENABLED) ? static_cast<uint32_t>(left_ > 0x7FFFFFFFull ? 0x7FFFFFFFull : left_) : 0u); \
+        RS[3] = 0x00020000u;                                                                 \
+    }
+// this wave's piece Q (0..3) of a tile into the stage at byte offset DST
+#define PK_COPY_PIECE(RS, DST, Q) lds_copy_16(RS, lds_wave + (DST) + (Q) * 1024, off.g[Q])
+#define PK_COPY_TILE(SRC, KSTART, DST, ENABLED)                                              \
+    {                                                                                        \
+        PK_TILE_DESC(rs_, SRC, KSTART, ENABLED)                                              \
+        _Pragma("unroll") for (int q = 0; q < 4; ++q) PK_COPY_PIECE(rs_, DST, q);            \
     }
 #define PK_WAIT_ALL_COPIES() __builtin_amdgcn_s_waitcnt(0x0F70)      /* vmcnt(0) */
 #define PK_CODE(INFO) (((INFO) >> (8 + 2 * u.wave)) & 3)          /* 0 skip, 1 masked, 2 unmasked */
@@ -205,23 +223,30 @@ __device__ __forceinline__ void lds_copy_16(const u32x4& rsrc, uint32_t lds_addr
 // Kernel A (default).  Two workgroups per CU (80 KiB of LDS each: three stages for K, two for V).
 // A key tile is handled as two halves of 32 keys, each with its own online-softmax step, so that
 // within one wave the matrix pipe and the vector ALU overlap without state that crosses tiles:
-//   phase 1   S0 = K(half 0) Q^T                                   (8 MFMAs)
-//   barrier   every copy requested one tile ago has landed; request V(j+1) and K(j+2)
+//   phase 1   S0 = K(half 0) Q^T      with the requests for V(j+1), K(j+2)   (8 MFMAs + 8 copies)
 //   phase 2   S1 = K(half 1) Q^T      with the softmax of S0       (8 MFMAs + vector work)
 //   phase 3   O += V(half 0)^T P0^T   with the softmax of S1       (8 MFMAs + vector work)
 //   phase 4   O += V(half 1)^T P1^T                                (8 MFMAs)
+//   barrier   this wave's copies have landed; every wave is done with the tile
 // The LDS operand reads of a phase are issued one phase ahead (the reads of phase 1 during phase 4
 // of the previous tile), into two register buffers of eight operands each.
+// Softmax state of a query row, in the exp2 domain (Q carries scale * log2 e):
+//   m_ref   reference that the exponentials are taken against; it only has to stay within 2^13
+//           of the running maximum, so it moves rarely ("lazy" rescaling);
+//   negm    sixteen copies of -m_ref: the S accumulators START there, so the MFMAs deliver
+//           s - m_ref and the softmax has no subtraction per score;
+//   m_set   the row has seen a key (m_ref means something);  l  this lane's share of the row sum.
+// Fast path of a half tile (16 scores per lane): p = exp2(s), pairs rounded to bf16, row sums by
+// dot2 -- four vector instructions per pair, no maximum.  The increment of the sum tells whether
+// the reference is still good: if any lane's increment exceeds 2^13 (or a row has no reference
+// yet) the whole wave redoes the half tile on the slow path below, which finds the maximum,
+// moves the reference and rescales.
 struct HalfSoftmax {
-    float mx, alpha, msl, l0, l1;
-    bool raise;
+    float l0, l1;
     uint32_t pw[8];
 };
-
-// Slice C (0..7) of the softmax of one half tile (16 scores per lane): two slices of maxima and
-// the decision, then the eight pairs of exponentials spread over six slices.
-__device__ constexpr int slice_first_pair(int c) { return c == 2 ? 0 : c == 3 ? 2 : c == 4 ? 3 : c == 5 ? 4 : c == 6 ? 6 : 7; }
-__device__ constexpr int slice_pairs(int c) { return c < 2 ? 0 : (c == 2 || c == 5) ? 2 : 1; }
+constexpr float kIncLimit = 8192.f;                // 2^13
+constexpr float kRaiseBy = 8.f;                    // a set reference is only raised by more than this
 
 // max without the canonicalising self-maximum that fmaxf() costs per operand (scores are never NaN;
 // -inf is ordinary here).  Not volatile: the compiler schedules these like any arithmetic.
@@ -236,60 +261,83 @@ __device__ __forceinline__ float max2f(float a, float b) {
     return r;
 }
 
+// Slice C (0..7) of the fast path: pair C of the half tile.
 template <int C>
-__device__ __forceinline__ void softmax_slice(const floatx16& s, HalfSoftmax& h, float& m, const float l,
-                                              float sl2, float lazy) {
-    if constexpr (C == 0) {
-        h.mx = max3f(max3f(max3f(max2f(s[0], s[1]), s[2], s[3]), s[4], s[5]), s[6], s[7]);
-    } else if constexpr (C == 1) {
-        float mx = max3f(max3f(max3f(max3f(h.mx, s[8], s[9]), s[10], s[11]), s[12], s[13]), s[14], s[15]);
-        const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
-        mx = max2f(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
-        h.raise = __builtin_amdgcn_ballot_w64(mx > m + lazy || m == -INFINITY) != 0;
-        const float m_new = h.raise ? max2f(m, mx) : m;
-        const float m_ref = (m_new == -INFINITY) ? 0.f : m_new;
-        h.alpha = __builtin_amdgcn_exp2f((m - m_ref) * sl2);   // m = -inf -> 0; unchanged m -> 1
-        m = m_new;
-        h.msl = m_ref * sl2;
-        h.l0 = l * h.alpha;
-        h.l1 = 0.f;
-    } else {
+__device__ __forceinline__ void softmax_slice(const floatx16& s, HalfSoftmax& h) {
+    floatx2 pp;
+    pp[0] = __builtin_amdgcn_exp2f(s[2 * C]);
+    pp[1] = __builtin_amdgcn_exp2f(s[2 * C + 1]);
+    const bf16x2 pb = __builtin_convertvector(pp, bf16x2);
+    // plain adds of the unrounded values: v_dot2c_f32_bf16 would sum the rounded pair in one
+    // instruction, but it stalls the matrix pipe (measured: 8 per 8 MFMAs cost as much as 4 MFMAs)
+    h.l0 += pp[0];
+    h.l1 += pp[1];
+    h.pw[C] = __builtin_bit_cast(uint32_t, pb);
+}
+
+// Slow path of a half tile (wave-uniform, rare): s holds the scores relative to the current
+// reference.  First the scalars: the row maximum (both lanes of a row agree through the swap),
+// the shift `delta` of the reference for the rows that need one, the factor alpha for what has
+// been accumulated so far.  The caller then shifts the scores, recomputes the probabilities and
+// rescales, each in a branch of its own that holds nothing but updates in place: written as one
+// block, the paths join with the 64 accumulators in fresh registers, more than the kernel has.
+__device__ __forceinline__ void softmax_slow_scalars(const floatx16& s, float& m_ref, bool& m_set,
+                                                     float& delta, float& alpha) {
+    float mx = max3f(max3f(max3f(max2f(s[0], s[1]), s[2], s[3]), s[4], s[5]), s[6], s[7]);
+    mx = max3f(max3f(max3f(max3f(mx, s[8], s[9]), s[10], s[11]), s[12], s[13]), s[14], s[15]);
+    const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+    mx = max2f(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+    const bool seen = mx > -INFINITY;              // the row has a visible key in this half tile
+    delta = (seen && (!m_set || mx > kRaiseBy)) ? mx : 0.f;
+    alpha = m_set ? __builtin_amdgcn_exp2f(-delta) : 1.f;   // nothing accumulated before the first key
+    m_set = m_set || seen;
+    m_ref += delta;
+}
+__device__ __forceinline__ void softmax_redo(floatx16& s, HalfSoftmax& h, float delta) {
+    h.l0 = 0.f; h.l1 = 0.f;
 #pragma unroll
-        for (int q = slice_first_pair(C); q < slice_first_pair(C) + slice_pairs(C); ++q) {
-            floatx2 pp;
-            pp[0] = __builtin_amdgcn_exp2f(fmaf(s[2 * q], sl2, -h.msl));
-            pp[1] = __builtin_amdgcn_exp2f(fmaf(s[2 * q + 1], sl2, -h.msl));
-            const bf16x2 pb = __builtin_convertvector(pp, bf16x2);
-            if (q & 1) h.l1 = __builtin_amdgcn_fdot2_f32_bf16(pb, bf16x2{(__bf16)1.0f, (__bf16)1.0f}, h.l1, false);
-            else h.l0 = __builtin_amdgcn_fdot2_f32_bf16(pb, bf16x2{(__bf16)1.0f, (__bf16)1.0f}, h.l0, false);
-            h.pw[q] = __builtin_bit_cast(uint32_t, pb);
-        }
+    for (int q = 0; q < 8; ++q) {
+        floatx2 pp;
+        pp[0] = __builtin_amdgcn_exp2f(s[2 * q] - delta);
+        pp[1] = __builtin_amdgcn_exp2f(s[2 * q + 1] - delta);
+        const bf16x2 pb = __builtin_convertvector(pp, bf16x2);
+        h.l0 += pp[0];
+        h.l1 += pp[1];
+        h.pw[q] = __builtin_bit_cast(uint32_t, pb);
     }
 }
+#define PK_SOFTMAX_CHECK(S, H, SHIFT_ALSO)                                                     \
+    {                                                                                          \
+        const bool slow = __builtin_amdgcn_ballot_w64((H.l0 + H.l1) > kIncLimit || !m_set) != 0; \
+        float delta = 0.f, alpha = 1.f;                                                        \
+        /* the empty asm statements keep the compiler from computing the rare branches always */ \
+        if (slow) { asm volatile(""); softmax_slow_scalars(S, m_ref, m_set, delta, alpha); }   \
+        if (slow) { asm volatile(""); softmax_redo(S, H, delta); }                             \
+        l = l * alpha + (H.l0 + H.l1);                                                         \
+        if (slow) {                                                                            \
+            _Pragma("unroll") for (int b = 0; b < DB; ++b)                                     \
+                _Pragma("unroll") for (int e = 0; e < 16; ++e) o[b][e] *= alpha;               \
+        }                                                                                      \
+        if (slow) {                                                                            \
+            _Pragma("unroll") for (int e = 0; e < 16; ++e) negm[e] = -m_ref;                   \
+        }                                                                                      \
+        SHIFT_ALSO                                                                             \
+    }
 
 // The compiler is free to move the (side-effect free) softmax arithmetic and the MFMAs of a phase
 // apart again.  Two empty volatile asm statements per slice tie them together: the first makes the
-// slice's inputs depend on the point after MFMA i (for the exponential slices through the
-// subtrahend they all share), the second makes the operand of MFMA i+1 depend on the point after
-// the slice's results.
+// slice's inputs depend on the point after MFMA i, the second makes the operand of MFMA i+1 depend
+// on the point after the slice's results.
 template <int C>
-__device__ __forceinline__ void pin_slice_inputs(floatx16& acc, HalfSoftmax& h) {
-    if constexpr (C < 2) asm volatile("" : "+v"(acc));
-    else asm volatile("" : "+v"(acc), "+v"(h.msl));
+__device__ __forceinline__ void pin_slice_inputs(floatx16& acc, floatx16& s) {
+    // (not after the first MFMA of a chain: tying its fresh result to the statement makes the
+    // compiler copy the sixteen start values into it instead of naming them as the C operand)
+    if constexpr (C == 0) asm volatile("" : "+v"(s));
+    else asm volatile("" : "+v"(acc), "+v"(s));
 }
 template <int C>
 __device__ __forceinline__ void pin_slice_outputs(bf16x8& next_operand, HalfSoftmax& h) {
-    if constexpr (C == 0) {
-        asm volatile("" : "+v"(next_operand), "+v"(h.mx));
-    } else if constexpr (C == 1) {
-        asm volatile("" : "+v"(next_operand), "+v"(h.msl), "+v"(h.l0), "+v"(h.alpha));
-    } else if constexpr (slice_pairs(C) == 2) {
-        constexpr int q = slice_first_pair(C);
-        asm volatile("" : "+v"(next_operand), "+v"(h.pw[q]), "+v"(h.pw[q + 1]), "+v"(h.l0), "+v"(h.l1));
-    } else {
-        constexpr int q = slice_first_pair(C);
-        asm volatile("" : "+v"(next_operand), "+v"(h.pw[q]), "+v"(h.l0), "+v"(h.l1));
-    }
+    asm volatile("" : "+v"(next_operand), "+v"(h.pw[C]), "+v"(h.l0), "+v"(h.l1));
 }
 
 // -inf for the keys of half `half` of a tile that a query row may not see (outside [lo, hi_t)):
@@ -326,8 +374,8 @@ __device__ __forceinline__ bf16x8 stream_operand(const unsigned char* k_cur, con
     {                                                                                          \
         constexpr int i = C;                                                                   \
         BODY;                                                                                  \
-        pin_slice_inputs<C>(ACC, H);                                                           \
-        softmax_slice<C>(S, H, m, l, sl2, lazy);                                               \
+        pin_slice_inputs<C>(ACC, S);                                                           \
+        softmax_slice<C>(S, H);                                                                \
         pin_slice_outputs<C>(ring[(C + 1) & 3], H);                                            \
     }
 // eight MFMAs (BODY, with accumulator ACC) interleaved with the softmax of the scores S
@@ -368,17 +416,20 @@ __global__ __launch_bounds__(256, 2) void prefill_bf16_dma_kernel(PrefillArgs a)
     for (int b = 0; b < DB; ++b)
 #pragma unroll
         for (int e = 0; e < 16; ++e) o[b][e] = 0.f;
-    float m = -INFINITY, l = 0.f;
-    const float sl2 = a.scale * kLog2e;
-    const float lazy = 8.0f / sl2;
+    // rows without a query count as "set" so that they never ask for the slow path
+    float m_ref = 0.f, l = 0.f;
+    bool m_set = u.qrow < 0;
+    floatx16 negm = {};
 
+    // this wave's quarter of a stage, as a scalar
+    const uint32_t lds_wave = __builtin_amdgcn_readfirstlane(lds_base + u.wave * 4096);
     // window of tile-list entries: e0 = tile j, e1 = tile j+1, e2 = tile j+2 (e3 is fetched for the next turn)
     int e0s, e0i, e1s, e1i, e2s, e2i;
     entry(0, e0s, e0i); entry(1, e1s, e1i); entry(2, e2s, e2i);
-    // prologue: K(0), K(1), V(0) (copies of tiles past the end are clamped duplicates into free stages)
-    PK_COPY_TILE(a.k, e0s, 0);
-    PK_COPY_TILE(a.k, e1s, TILE_BYTES);
-    PK_COPY_TILE(a.v, e0s, 3 * TILE_BYTES);
+    // prologue: K(0), K(1), V(0)
+    PK_COPY_TILE(a.k, e0s, 0, true);
+    PK_COPY_TILE(a.k, e1s, TILE_BYTES, 1 < n_kv);
+    PK_COPY_TILE(a.v, e0s, 3 * TILE_BYTES, true);
     PK_WAIT_ALL_COPIES();
     __syncthreads();
 
@@ -387,27 +438,37 @@ __global__ __launch_bounds__(256, 2) void prefill_bf16_dma_kernel(PrefillArgs a)
     for (int x = 0; x < 4; ++x) ring[x] = k_operand(lds, off, 0, x);
     int k_cur = 0, k_next = TILE_BYTES, k_fill = 2 * TILE_BYTES;   // K stage read now / next / filled now
     int v_cur = 3 * TILE_BYTES, v_fill = 4 * TILE_BYTES;
-    const floatx16 zero = {};
-    // After the barrier of tile j every wave is done with tile j-1, so the stages of K(j-1) and
-    // V(j-1) are refilled with V(j+1) and K(j+2); the copies requested one tile ago must have
-    // landed (only they matter: the compiler's own barrier would also wait for the LDS reads).
-#define PK_BARRIER_AND_REFILL()                                                               \
-    asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");                              \
-    if (j + 1 < n_kv) PK_COPY_TILE(a.v, e1s, v_fill);                                          \
-    if (j + 2 < n_kv) PK_COPY_TILE(a.k, e2s, k_fill);                                          \
+    // Tile j: while S0 is computed, V(j+1) and K(j+2) are requested into the stages of V(j-1) and
+    // K(j-1), one 1-KiB piece behind each of the eight MFMAs, where their issue costs nothing.  The
+    // barrier at the END of the tile (after this wave's copies have landed: only they matter, the
+    // compiler's own barrier would also wait for the LDS reads) says that every wave is done with
+    // tile j and that V(j+1) and K(j+2) are complete; K(j+1), whose first operands are read during
+    // the last MFMAs of tile j, was published a tile earlier.
+#define PK_TILE_BEGIN()                                                                       \
+    PK_TILE_DESC(rs_k, a.k, e2s, j + 2 < n_kv)                                                 \
+    PK_TILE_DESC(rs_v, a.v, e1s, j + 1 < n_kv)
+#define PK_COPY_STEP(I)                                                                       \
+    if constexpr ((I) < 4) PK_COPY_PIECE(rs_k, k_fill, (I));                                   \
+    else PK_COPY_PIECE(rs_v, v_fill, (I) - 4);
+    // (the next list entry is fetched right before the barrier: scalar loads and LDS reads share a
+    // counter and return out of order, so the first wait after the fetch drains the operand ring;
+    // here the ring has the whole barrier to land anyway)
+#define PK_TILE_END()                                                                         \
     int e3s, e3i;                                                                              \
-    entry(j + 3, e3s, e3i);
-#define PK_ROTATE()                                                                           \
+    entry(j + 3, e3s, e3i);                                                                    \
+    asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");                              \
     e0s = e1s; e0i = e1i; e1s = e2s; e1i = e2i; e2s = e3s; e2i = e3i;                          \
     { const int kc = k_cur; k_cur = k_next; k_next = k_fill; k_fill = kc; }                    \
     { const int vc = v_cur; v_cur = v_fill; v_fill = vc; }
 
     int j = 0;
-    // leading tiles that this wave skips: it only takes part in the barriers and in the copies,
+    // leading tiles that this wave skips: it only takes part in the copies and in the barriers,
     // then picks up its first operands from the stage that is current by then
     for (; j < u.n_lead; ++j) {
-        PK_BARRIER_AND_REFILL();
-        PK_ROTATE();
+        PK_TILE_BEGIN();
+#pragma unroll
+        for (int q = 0; q < 4; ++q) { PK_COPY_PIECE(rs_k, k_fill, q); PK_COPY_PIECE(rs_v, v_fill, q); }
+        PK_TILE_END();
     }
     if (u.n_lead > 0) {
 #pragma unroll
@@ -418,47 +479,40 @@ __global__ __launch_bounds__(256, 2) void prefill_bf16_dma_kernel(PrefillArgs a)
         const bool masked = PK_CODE(e0i) != 2;
         const int k_start = e0s;
         const int hi_t = min(u.hi, k_start + (e0i & 0xFF));   // keys past the tile's valid count are foreign
+        PK_TILE_BEGIN();
         floatx16 s0, s1;
-        PK_EIGHT(s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[i & 3], qf[i], i == 0 ? zero : s0, 0, 0, 0);
-                 PK_REFILL(0));
-        PK_BARRIER_AND_REFILL();
+        PK_EIGHT(s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[i & 3], qf[i], i == 0 ? negm : s0, 0, 0, 0);
+                 PK_REFILL(0); PK_COPY_STEP(i));
         HalfSoftmax h0, h1;
+        h0.l0 = 0.f; h0.l1 = 0.f; h1.l0 = 0.f; h1.l1 = 0.f;
         if (masked) mask_half(s0, 0, u.lo, hi_t, k_start, u.hlf);    // unmasked tiles skip the compares
-        PK_SLICES(s0, h0, s1, s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[i & 3], qf[i], i == 0 ? zero : s1, 0, 0, 0);
+        PK_SLICES(s0, h0, s1, s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[i & 3], qf[i], i == 0 ? negm : s1, 0, 0, 0);
                   PK_REFILL(8));
-        l = h0.l0 + h0.l1;
+        PK_SOFTMAX_CHECK(s0, h0, if (slow) {                      /* S1 was started at the old reference */
+            _Pragma("unroll") for (int e = 0; e < 16; ++e) s1[e] -= delta;
+        })
         bf16x8 p0[2], p1[2];
 #pragma unroll
         for (int t = 0; t < 2; ++t)
             p0[t] = __builtin_bit_cast(bf16x8, u32x4{h0.pw[4 * t], h0.pw[4 * t + 1], h0.pw[4 * t + 2], h0.pw[4 * t + 3]});
-        if (h0.raise) {                              // rare: the stored maximum was raised
-#pragma unroll
-            for (int b = 0; b < DB; ++b)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) o[b][e] *= h0.alpha;
-        }
         if (masked) mask_half(s1, 1, u.lo, hi_t, k_start, u.hlf);
         PK_SLICES(s1, h1, o[i & 3], o[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[i & 3], p0[i >> 2], o[i & 3], 0, 0, 0);
                   PK_REFILL(16));
-        l = h1.l0 + h1.l1;
+        PK_SOFTMAX_CHECK(s1, h1, )
 #pragma unroll
         for (int t = 0; t < 2; ++t)
             p1[t] = __builtin_bit_cast(bf16x8, u32x4{h1.pw[4 * t], h1.pw[4 * t + 1], h1.pw[4 * t + 2], h1.pw[4 * t + 3]});
-        if (h1.raise) {
-#pragma unroll
-            for (int b = 0; b < DB; ++b)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) o[b][e] *= h1.alpha;
-        }
-        // phase 4; its last refills are the first operands of the next tile (K(j+1) landed before the barrier)
+        // phase 4; its last refills are the first operands of the next tile
         PK_EIGHT(o[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[i & 3], p1[i >> 2], o[i & 3], 0, 0, 0);
                  PK_REFILL(24));
-        PK_ROTATE();
+        PK_TILE_END();
     }
-    // trailing tiles that this wave skips: it only takes part in the barriers and in the copies
+    // trailing tiles that this wave skips: it only takes part in the copies and in the barriers
     for (; j < n_kv; ++j) {
-        PK_BARRIER_AND_REFILL();
-        PK_ROTATE();
+        PK_TILE_BEGIN();
+#pragma unroll
+        for (int q = 0; q < 4; ++q) { PK_COPY_PIECE(rs_k, k_fill, q); PK_COPY_PIECE(rs_v, v_fill, q); }
+        PK_TILE_END();
     }
     // After the last barrier nobody reads or fills the two stages that would have taken tiles
     // n_kv and n_kv + 1 (after the final rotation: k_next and v_cur), and a wave's copies only
@@ -469,8 +523,12 @@ __global__ __launch_bounds__(256, 2) void prefill_bf16_dma_kernel(PrefillArgs a)
 }
 
 #undef PK_COPY_TILE
-#undef PK_BARRIER_AND_REFILL
-#undef PK_ROTATE
+#undef PK_TILE_DESC
+#undef PK_COPY_PIECE
+#undef PK_COPY_STEP
+#undef PK_SOFTMAX_CHECK
+#undef PK_TILE_BEGIN
+#undef PK_TILE_END
 #undef PK_SLICE
 #undef PK_SLICES
 #undef PK_EIGHT
