@@ -3,21 +3,28 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--seed S] [--no-extras]
 
-Prints ONE JSON line.  Headline workload: the Llama-3-8B-shaped prefill
-attention layer (64 requests, lognormal lengths, 32 query / 8 KV heads,
-head_dim 128, bf16, causal, token budget 16384).  A step is one pass of the
-hot path over that batch: pack_plan on the host, the copy of the plan's
-integer tables to the device, and the packed prefill kernel.  Inputs are
-resident in HBM before the timed region starts.
+Prints ONE JSON line.  Headline workload: the mixed continuous-batching step of
+the Llama-3-70B-shaped attention layer (configs[4]: 64 query / 8 KV heads,
+head_dim 128, bf16; 32 chunked-prefill chunks of 512..2048 tokens with prior
+context 0..16384, plus 480 decode rows over paged KV of 128..65536 tokens), the
+largest single-GPU configuration.  A step is one pass of the whole hot path
+over that batch: pack_plan for the prefill part and for the decode part on the
+host, the copies of the plans' integer tables to the device, the KV re-layout
+of the decode batch into group-contiguous buffers, the packed prefill kernel,
+the packed decode kernel and its LSE merge.  Inputs are resident in HBM before
+the timed region starts.
 
-  value     whole-step throughput in TFLOP/s: algorithmic flops
-            (4 * d * Hq * unmasked pairs) / wall time of the timed steps
-  roofline  packed prefill kernel alone (HIP events on the launch stream),
-            against the dense bf16 MFMA peak
+  value     whole-step throughput in TFLOP/s: algorithmic prefill flops
+            (4 * d * Hq * unmasked pairs) / wall time of the timed steps (the
+            decode and re-layout parts add time, not flops: they are HBM-bound
+            and reported in GB/s)
+  roofline  the dominant kernel (packed prefill) against the dense bf16 MFMA
+            peak, its duration measured with HIP events inside the timed steps;
+            roofline_decode / roofline_relayout: the HBM-bound kernels of the
+            same steps against 8 TB/s
   cpu_baseline  the CPU oracle timed on a bounded sample of the same batch
-  extra     the in-run padded baseline, planner time, and the decode /
-            re-layout / shared-prefix / mixed-step workloads with their own
-            HBM roofline fractions
+  extra     the in-run padded baselines, planner times, and configurations
+            1-4 with their own roofline fractions
 
 More than one GPU is not supported: this path has no sharding or collectives.
 """
@@ -235,6 +242,76 @@ def bench_multistep(w, steps=32):
             "token_budget": int(w.token_budget)}
 
 
+def regroup_bench(wl, pk, seed, dev, T=96):
+    """Decode loops of T steps on configuration 3 that honour the regrouping triggers (Sec. 3.1
+    "Adaptive Grouping", Eq. 4; Sec. 3.2 headroom): append -> decode -> pk_regroup_due; when a trigger
+    of the policy is set, a new plan is made from the grown lengths and the buffer is re-organised from
+    the paged pool (which the engine's cache write keeps complete).  Reports the cost per step with the
+    rule in force and the cadence observed, for several (C, headroom, policy) settings."""
+    import torch
+    lens0 = wl.config3_lengths(seed)
+    w = wl.make_paged("regroup_cfg3", lens0 + T, 32, 8, 128, 8192, 16, seed, device=dev)
+    ones = np.ones(w.n, dtype=np.int32)
+    bt = torch.from_numpy(w.block_table).to(dev)
+    btl = bt.long()
+    req = torch.arange(w.n, device=dev)
+    g = torch.Generator(device=dev).manual_seed(5)
+    q = torch.randn(w.q.shape, generator=g, device=dev).to(torch.bfloat16)
+    out = torch.empty(w.q.shape, dtype=torch.bfloat16, device=dev)
+    # the K/V rows of the generated tokens, as the model would hand them over step by step
+    new_k, new_v = [], []
+    for s in range(T):
+        pos = torch.from_numpy((lens0 + s).astype(np.int64)).to(dev)
+        blk = btl[req, pos // w.page_size]
+        new_k.append(w.k_pages[blk, pos % w.page_size].contiguous())
+        new_v.append(w.v_pages[blk, pos % w.page_size].contiguous())
+    policies = {"eq4_within_budget_or_headroom": pk.REGROUP_DRIFT_WITHIN_BUDGET | pk.REGROUP_HEADROOM,
+                "headroom_only": pk.REGROUP_HEADROOM,
+                "eq4_literal_or_headroom": pk.REGROUP_DRIFT | pk.REGROUP_HEADROOM}
+    res = {"steps": T, "requests": int(w.n), "kv_tokens_at_start": int(lens0.sum()),
+           "note": "cadence of the paper's workloads (every 20-40 steps at C = 8192) is parity unpinned: the traces are not "
+                   "available; this heavy-tailed batch leaves groups of very different member counts, so Eq. 4 fires early"}
+    for C, headroom in ((8192, 32), (16384, 32)):
+        for name, policy in policies.items():
+            def loop(record=None):
+                lens = lens0.copy()
+                plan = pk.pack_plan(lens, ones, None, None, C, headroom)
+                ws = pk.new_workspace(plan, w.Hq, w.Hkv, w.d, pk.PK_BF16)
+                buf = pk.new_kv_buf(plan, w.Hkv, w.d, pk.PK_BF16)
+                pk.kv_reorganize(plan, w.k_pages, w.v_pages, bt, buf, ws)
+                t = 0
+                for s in range(T):
+                    pk.kv_append(plan, new_k[s], new_v[s], buf, t, ws)
+                    t += 1
+                    pk.packed_decode_attn_grown(plan, q, buf, out, w.scale, t, w.Hkv, ws)
+                    if pk.regroup_due(plan, t)[0] & policy and s + 1 < T:
+                        if record is not None:
+                            record.append(s)
+                        lens = lens0 + (s + 1)
+                        plan2 = pk.pack_plan(lens, ones, None, None, C, headroom)
+                        ws2 = pk.new_workspace(plan2, w.Hq, w.Hkv, w.d, pk.PK_BF16)
+                        if plan2.kv_buf_bytes(w.Hkv, w.d, pk.PK_BF16) > buf.numel():
+                            buf = pk.new_kv_buf(plan2, w.Hkv, w.d, pk.PK_BF16)
+                        pk.kv_reorganize(plan2, w.k_pages, w.v_pages, bt, buf, ws2)
+                        keep.append((plan, ws))           # alive until their launches have run
+                        plan, ws, t = plan2, ws2, 0
+                keep.append((plan, ws))
+            keep, fired = [], []
+            loop(fired)
+            torch.cuda.synchronize()
+            keep.clear()
+            t0 = time.perf_counter()
+            loop()
+            torch.cuda.synchronize()
+            wall = time.perf_counter() - t0
+            keep.clear()
+            gaps = np.diff([-1] + fired) if fired else np.array([T])
+            res[f"C{C}_headroom{headroom}_{name}"] = {
+                "regroups": len(fired), "steps_between_regroups_mean": float(np.mean(gaps)),
+                "first_regroups_at_steps": fired[:6], "ms_per_step_all_in": wall / T * 1e3}
+    return res
+
+
 def capacity_sweep(wl, pk, seed, dev):
     """Offline profiling of the group capacity C (Sec. 3.1 "Adaptive Grouping": C is found by
     profiling a range of group lengths): packed prefill kernel time and issued/useful work on
@@ -267,7 +344,29 @@ def capacity_sweep(wl, pk, seed, dev):
                     "reorg_ms": r_ms, "decode_ms": d_ms})
         rows.append(row)
         del buf, ws3, ws
-    return rows
+    # the decode split (tokens per split-KV work item) at C = 16384: the other schedule parameter
+    # that is found by profiling; 0 = the builder's own choice
+    splits = []
+    w4 = wl.config4(seed, device=dev)
+    out4 = torch.empty(w4.q.shape, dtype=torch.bfloat16, device=dev)
+    bt4 = torch.from_numpy(w4.block_table).to(dev)
+    for sp in (0, 128, 256, 512, 1024, 2048, 4096):
+        row = {"decode_split_tokens_requested": sp}
+        for tag, w, o, b in (("cfg3", w3, out3, bt), ("cfg4", w4, out4, bt4)):
+            plan = pk.pack_plan(w.kv_lens, np.ones_like(w.kv_lens), w.prefix_ids, w.prefix_lens, 16384)
+            plan.tune(pk.TUNE_DECODE_SPLIT, sp)
+            ws = pk.new_workspace(plan, w.Hq, w.Hkv, w.d, pk.PK_BF16)
+            pk.plan_bind(plan, w.Hq, w.Hkv, w.d, pk.PK_BF16, ws)
+            buf = pk.new_kv_buf(plan, w.Hkv, w.d, pk.PK_BF16)
+            pk.kv_reorganize(plan, w.k_pages, w.v_pages, b, buf, ws)
+            ms, _ = _time_launches(lambda: pk.packed_decode_attn(plan, w.q, buf, o, w.scale, w.Hkv, ws), 30)
+            row.update({f"{tag}_split_used": plan.stat(5), f"{tag}_work_items": plan.stat(3),
+                        f"{tag}_partials": plan.stat(4), f"{tag}_decode_ms": ms})
+            del buf, ws
+        splits.append(row)
+    return {"capacity": rows, "decode_split": splits,
+            "prefill_tile_shape": "128 query rows x 64 keys per workgroup step (4 waves x 32 rows, two key halves of 32): "
+                                  "fixed at compile time by the register budget of the MFMA scheme, not swept"}
 
 
 def prefix_tree_bench(wl, pk, seed, dev):
@@ -366,29 +465,105 @@ def motivation_replay(wl, pk, seed, dev):
     return res
 
 
-def cpu_baseline(w):
-    """The oracle as it stands, timed on every second query row of the batch."""
-    from oracle import attention as oa
-    rows = np.array([(i, h, t) for i in range(w.n) for t in range(0, int(w.q_lens[i]), 2)
-                     for h in range(w.Hq)], dtype=np.int32)
-    ctx = (w.kv_lens - w.q_lens).astype(np.int64)
-    pairs = int(sum(int(ctx[i]) + int(t) + 1 for (i, _, t) in rows))
-    q, k, v = w.q.cpu(), w.k.cpu(), w.v.cpu()
+def bench_mixed(w5, steps, warmup, with_padded=True):
+    """The mixed step of configuration 5: every row of the hot path once per step, kernels timed with HIP
+    events on the launch stream inside the timed steps."""
+    import torch
+    from paper_2602_06072_amd import binding as pk
+    p, d = w5.prefill, w5.decode
+    dev = p.q.device
+    ones = np.ones_like(d.kv_lens)
+    out_p = torch.empty(p.q.shape, dtype=torch.bfloat16, device=dev)
+    out_d = torch.empty(d.q.shape, dtype=torch.bfloat16, device=dev)
+    plan_p0 = pk.pack_plan(p.kv_lens, p.q_lens, token_budget=p.token_budget)
+    plan_d0 = pk.pack_plan(d.kv_lens, ones, d.prefix_ids, d.prefix_lens, d.token_budget)
+    ws_p = pk.new_workspace(plan_p0, p.Hq, p.Hkv, p.d, pk.PK_BF16)
+    ws_d = pk.new_workspace(plan_d0, d.Hq, d.Hkv, d.d, pk.PK_BF16)
+    kv_buf = pk.new_kv_buf(plan_d0, d.Hkv, d.d, pk.PK_BF16)
+    bt = torch.from_numpy(d.block_table).to(dev)
+    pairs = plan_p0.stat(0)
+    flops = prefill_flops(p, pairs)
+    kv_bytes = plan_d0.unique_tokens * d.Hkv * d.d * 2 * 2
+
+    def step(ev=None):
+        plan_p = pk.pack_plan(p.kv_lens, p.q_lens, token_budget=p.token_budget)
+        plan_d = pk.pack_plan(d.kv_lens, ones, d.prefix_ids, d.prefix_lens, d.token_budget)
+        pk.plan_bind(plan_p, p.Hq, p.Hkv, p.d, pk.PK_BF16, ws_p)
+        pk.plan_bind(plan_d, d.Hq, d.Hkv, d.d, pk.PK_BF16, ws_d)
+        if ev: ev[0].record()
+        pk.kv_reorganize(plan_d, d.k_pages, d.v_pages, bt, kv_buf, ws_d)
+        if ev: ev[1].record()
+        pk.packed_prefill_attn(plan_p, p.q, p.k, p.v, out_p, p.scale, ws_p)
+        if ev: ev[2].record()
+        pk.packed_decode_attn(plan_d, d.q, kv_buf, out_d, d.scale, d.Hkv, ws_d)
+        if ev: ev[3].record()
+        return plan_p, plan_d
+
+    keep = [step() for _ in range(warmup)]          # plans stay alive until their copies have run
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(steps)]
     t0 = time.perf_counter()
-    _, used = oa.attention_ragged(q, k, v, w.q_lens, w.kv_lens, w.scale, rows=rows)
+    keep = [step(evs[i]) for i in range(steps)]
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    del keep
+    reorg_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in evs]))
+    prefill_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in evs]))
+    decode_ms = float(np.mean([e[2].elapsed_time(e[3]) for e in evs]))
+    pk.plan_bind(plan_d0, d.Hq, d.Hkv, d.d, pk.PK_BF16, ws_d)
+    n_parts = plan_d0.stat(4)
+    dec_bytes = kv_bytes + d.n * d.Hq * d.d * 4 + 2 * n_parts * d.Hq * (d.d + 1) * 4
+    res = {"ms_per_step": wall / steps * 1e3, "step_tflops": flops * steps / wall / 1e12,
+           "prefill_kernel_ms": prefill_ms, "prefill_kernel_tflops": flops / (prefill_ms * 1e-3) / 1e12,
+           "prefill_flops": flops, "prefill_pairs": pairs,
+           "decode_ms_incl_merge": decode_ms, "decode_alg_bytes": dec_bytes,
+           "decode_gbs": dec_bytes / (decode_ms * 1e-3) / 1e9,
+           "relayout_ms": reorg_ms, "relayout_alg_bytes": 2 * kv_bytes,
+           "relayout_gbs": 2 * kv_bytes / (reorg_ms * 1e-3) / 1e9,
+           "host_and_gaps_ms": wall / steps * 1e3 - reorg_ms - prefill_ms - decode_ms,
+           "prefill_q_tokens": int(p.q_lens.sum()), "prefill_kv_tokens": int(p.kv_lens.sum()),
+           "decode_requests": int(d.n), "decode_kv_tokens": int(d.kv_lens.sum()),
+           "decode_work_items": plan_d0.stat(3), "decode_split_tokens": plan_d0.stat(5),
+           "prefill_useful_over_issued_packed": pairs / max(1, plan_p0.stat(1)),
+           "prefill_useful_over_issued_padded": pairs / max(1, plan_p0.stat(2)),
+           "ms_per_step_with_relayout_amortised_over_32_steps": wall / steps * 1e3 - reorg_ms * 31.0 / 32.0}
+    if with_padded:
+        pk.plan_bind(plan_p0, p.Hq, p.Hkv, p.d, pk.PK_BF16, ws_p)
+        pad_p, _ = _time_launches(lambda: pk.padded_prefill_attn(plan_p0, p.q, p.k, p.v, out_p, p.scale, ws_p), 5, warmup=1)
+        pad_d, _ = _time_launches(lambda: pk.padded_decode_attn(plan_d0, d.q, d.k_pages, d.v_pages, bt, out_d, d.scale, ws_d), 5, warmup=1)
+        res.update({"padded_prefill_kernel_ms": pad_p, "padded_decode_ms": pad_d,
+                    "padded_over_packed_prefill": pad_p / prefill_ms, "padded_over_packed_decode": pad_d / decode_ms,
+                    "padded_step_kernels_ms": pad_p + pad_d, "packed_step_kernels_ms": prefill_ms + decode_ms})
+    return res
+
+
+def cpu_baseline(p):
+    """The oracle as it stands, timed on every 8th query row (all heads) of the prefill part of the batch."""
+    from oracle import attention as oa
+    stride = 8
+    rows = np.array([(i, h, t) for i in range(p.n) for t in range(0, int(p.q_lens[i]), stride)
+                     for h in range(p.Hq)], dtype=np.int32)
+    ctx = (p.kv_lens - p.q_lens).astype(np.int64)
+    per_row = np.array([int(ctx[i]) + int(t) + 1 for i in range(p.n) for t in range(0, int(p.q_lens[i]), stride)], dtype=np.int64)
+    pairs = int(per_row.sum()) * p.Hq
+    q, k, v = p.q.cpu(), p.k.cpu(), p.v.cpu()
+    t0 = time.perf_counter()
+    _, used = oa.attention_ragged(q, k, v, p.q_lens, p.kv_lens, p.scale, rows=rows)
     dt = time.perf_counter() - t0
-    return {"value": 4.0 * w.d * pairs / dt / 1e12, "unit": "TFLOP/s", "cores": int(used), "kind": "oracle",
-            "sample": f"every 2nd query row of every request, all {w.Hq} heads "
-                      f"({len(rows)} rows, {4.0 * w.d * pairs / 1e9:.1f} GFLOP, {dt:.1f} s, fp64 accumulate)"}
+    return {"value": 4.0 * p.d * pairs / dt / 1e12, "unit": "TFLOP/s", "cores": int(used), "kind": "oracle",
+            "sample": f"prefill part of configs[4]: every {stride}th query row of every chunk, all {p.Hq} heads "
+                      f"({len(rows)} rows, {4.0 * p.d * pairs / 1e9:.1f} GFLOP, {dt:.1f} s, fp64 accumulate)"}
 
 
-def profiled_traffic(tag):
-    """HBM bytes per launch measured with rocprofv3 counters (profiles/bench_hbm_traffic.txt), or None."""
+def profiled(tag, field):
+    """A figure from the committed rocprofv3 summary (profiles/bench_hbm_traffic.txt), or None."""
     try:
         for line in open(os.path.join(ROOT, "profiles", "bench_hbm_traffic.txt")):
             f = line.split()
             if len(f) >= 5 and f[0] == "TRAFFIC" and f[1] == tag:
-                return float(f[4].split("=")[1])
+                for x in f[2:]:
+                    if x.startswith(field + "="):
+                        return float(x.split("=")[1])
     except OSError:
         pass
     return None
@@ -397,10 +572,10 @@ def profiled_traffic(tag):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=100)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--seed", type=int, default=0)
-    ap.add_argument("--no-extras", action="store_true", help="skip the decode / mixed-step lines")
+    ap.add_argument("--no-extras", action="store_true", help="only the headline workload")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain elementwise kernel over 1 GiB 5 times (reference for HBM byte counters)")
@@ -409,7 +584,9 @@ def main():
     ap.add_argument("--prefix-tree", action="store_true",
                     help="instead of the benchmark line: decode with no / one-level / nested shared prefixes (one JSON line)")
     ap.add_argument("--capacity-sweep", action="store_true",
-                    help="instead of the benchmark line: profile the group capacity C over a range (one JSON line)")
+                    help="instead of the benchmark line: profile the group capacity C and the decode split over a range (one JSON line)")
+    ap.add_argument("--regroup", action="store_true",
+                    help="instead of the benchmark line: decode loops that re-plan when the rule of Eq. 4 or the headroom says so (one JSON line)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this hot path runs on ONE GPU (no sharding, no collectives); use --gpus 1",
@@ -436,6 +613,9 @@ def main():
         print(json.dumps({"capacity_sweep": capacity_sweep(wl, pk, args.seed, dev), "seed": args.seed,
                           "workloads": "configs[1] prefill, configs[2] decode"}))
         return
+    if args.regroup:
+        print(json.dumps({"regroup_loop": regroup_bench(wl, pk, args.seed, dev), "seed": args.seed}))
+        return
 
     if args.calibrate_copy:
         # an elementwise kernel that reads 1 GiB and writes 1 GiB (bf16 x 2 -> bf16)
@@ -445,10 +625,49 @@ def main():
             torch.mul(src, 2.0, out=dst)
         torch.cuda.synchronize()
         del src, dst
-    w2 = wl.config2(args.seed, device=dev)
-    r2 = bench_prefill(w2, args.steps, args.warmup)
-    extra = {"prefill_cfg2": r2}
+    w5 = wl.config5(args.seed, device=dev)
+    m = bench_mixed(w5, args.steps, args.warmup)
+    line = {
+        "metric": "packed attn prefill TFLOP/s + decode KV GB/s (% roofline) vs padded",
+        "value": m["step_tflops"], "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": m["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "configs[4]: mixed continuous-batching step, Llama-3-70B-shaped attention (Hq=64 Hkv=8 d=128, "
+                               "bf16, causal): 32 chunked-prefill chunks of [512,2048] tokens with prior context [0,16384] + "
+                               "480 decode rows, KV 80% [128,2048] / 20% [16384,65536], paged in 16-token blocks; token budget 16384",
+                   "seed": args.seed, "prefill_q_tokens": m["prefill_q_tokens"], "decode_kv_tokens": m["decode_kv_tokens"],
+                   "step": "pack_plan x2 + table uploads + kv_reorganize (decode batch) + packed prefill kernel + "
+                           "packed decode kernel + LSE merge; value = prefill flops / step time"},
+        "roofline": {"bound": "mfma", "achieved": m["prefill_kernel_tflops"], "peak": MFMA_BF16_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": m["prefill_kernel_tflops"] / MFMA_BF16_PEAK_TFLOPS,
+                     "traffic": profiled("prefill_cfg5_packed", "total_bytes") if args.seed == 0 else None,
+                     "traffic_source": "profiles/bench_hbm_traffic.txt (rocprofv3 counters of an earlier run of this command, not this run)",
+                     "kernel": "prefill_bf16_dma_kernel", "kernel_ms": m["prefill_kernel_ms"],
+                     "flops_per_launch": m["prefill_flops"]},
+        "roofline_decode": {"bound": "hbm", "achieved": m["decode_gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                            "frac": m["decode_gbs"] / HBM_PEAK_GBS,
+                            "traffic": profiled("decode_cfg5", "total_bytes") if args.seed == 0 else None,
+                            "kernel": "decode_bf16_kernel<128> + decode_merge_kernel<128, 4>",
+                            "kernel_ms": m["decode_ms_incl_merge"], "bytes_per_launch": m["decode_alg_bytes"]},
+        "roofline_relayout": {"bound": "hbm", "achieved": m["relayout_gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                              "frac": m["relayout_gbs"] / HBM_PEAK_GBS,
+                              "traffic": profiled("reorg_cfg5", "total_bytes") if args.seed == 0 else None,
+                              "kernel": "reorg_bf16_kernel<128>", "kernel_ms": m["relayout_ms"],
+                              "bytes_per_launch": m["relayout_alg_bytes"]},
+    }
+    if not args.no_cpu:
+        line["cpu_baseline"] = cpu_baseline(w5.prefill)
+    extra = {"mixed_cfg5": m}
+    del w5
+    torch.cuda.empty_cache()
     if not args.no_extras:
+        w1 = wl.config1(args.seed, device=dev)
+        extra["prefill_cfg1_tiny"] = bench_prefill(w1, 50, 20)
+        del w1
+        w2 = wl.config2(args.seed, device=dev)
+        extra["prefill_cfg2"] = bench_prefill(w2, 100, 50)
+        del w2
         w3 = wl.config3(args.seed, device=dev)
         extra["decode_cfg3"] = bench_decode(w3, 20)
         extra["decode_cfg3_32_steps"] = bench_multistep(w3, 32)
@@ -458,28 +677,6 @@ def main():
         del w4
         extra["decode_nested_prefixes"] = prefix_tree_bench(wl, pk, args.seed, dev)
         torch.cuda.empty_cache()
-        w5 = wl.config5(args.seed, device=dev)
-        extra["prefill_cfg5_70b_chunks"] = bench_prefill(w5.prefill, 5, 2)
-        extra["decode_cfg5_70b"] = bench_decode(w5.decode, 5)
-        del w5
-        torch.cuda.empty_cache()
-    line = {
-        "metric": "packed attn prefill TFLOP/s + decode KV GB/s (% roofline) vs padded",
-        "value": r2["step_tflops"], "unit": "TFLOP/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": r2["ms_per_step"], "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "configs[1]: Llama-3-8B-shaped prefill attention layer, 64 requests, "
-                               "lognormal lengths (median 256, sigma 1.2, clip [8,8192]), Hq=32 Hkv=8 d=128, "
-                               "causal, token budget 16384", "seed": args.seed,
-                   "tokens": int(w2.q_lens.sum()), "step": "pack_plan + table upload + packed prefill kernel"},
-        "roofline": {"bound": "mfma", "achieved": r2["kernel_tflops"], "peak": MFMA_BF16_PEAK_TFLOPS,
-                     "unit": "TFLOP/s", "frac": r2["kernel_tflops"] / MFMA_BF16_PEAK_TFLOPS,
-                     "traffic": profiled_traffic("prefill_cfg2_packed") if args.seed == 0 else None,
-                     "kernel": "prefill_bf16_dma_kernel", "kernel_ms": r2["kernel_ms"]},
-    }
-    if not args.no_cpu:
-        line["cpu_baseline"] = cpu_baseline(w2)
     line["extra"] = extra
     print(json.dumps(line))
 
