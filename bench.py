@@ -527,6 +527,30 @@ def bench_mixed(w5, steps, warmup, with_padded=True):
            "prefill_useful_over_issued_packed": pairs / max(1, plan_p0.stat(1)),
            "prefill_useful_over_issued_padded": pairs / max(1, plan_p0.stat(2)),
            "ms_per_step_with_relayout_amortised_over_32_steps": wall / steps * 1e3 - reorg_ms * 31.0 / 32.0}
+    # the same step with the prefill tiles and the decode work items in ONE launch (pk_packed_mixed_step)
+    def fused_step(ev=None):
+        plan_p = pk.pack_plan(p.kv_lens, p.q_lens, token_budget=p.token_budget)
+        plan_d = pk.pack_plan(d.kv_lens, ones, d.prefix_ids, d.prefix_lens, d.token_budget)
+        pk.plan_bind(plan_p, p.Hq, p.Hkv, p.d, pk.PK_BF16, ws_p)
+        pk.plan_bind(plan_d, d.Hq, d.Hkv, d.d, pk.PK_BF16, ws_d)
+        pk.kv_reorganize(plan_d, d.k_pages, d.v_pages, bt, kv_buf, ws_d)
+        if ev: ev[0].record()
+        pk.packed_mixed_step(plan_p, p.q, p.k, p.v, out_p, ws_p, plan_d, d.q, kv_buf, out_d, ws_d, p.scale)
+        if ev: ev[1].record()
+        return plan_p, plan_d
+
+    keep = [fused_step() for _ in range(max(2, warmup // 2))]
+    torch.cuda.synchronize()
+    fevs = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(steps)]
+    t0 = time.perf_counter()
+    keep = [fused_step(fevs[i]) for i in range(steps)]
+    torch.cuda.synchronize()
+    fwall = time.perf_counter() - t0
+    del keep
+    fused_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in fevs]))
+    res.update({"fused_ms_per_step": fwall / steps * 1e3, "fused_step_tflops": flops * steps / fwall / 1e12,
+                "fused_prefill_plus_decode_ms": fused_ms, "separate_prefill_plus_decode_ms": prefill_ms + decode_ms,
+                "fused_over_separate": fused_ms / (prefill_ms + decode_ms)})
     if with_padded:
         pk.plan_bind(plan_p0, p.Hq, p.Hkv, p.d, pk.PK_BF16, ws_p)
         pad_p, _ = _time_launches(lambda: pk.padded_prefill_attn(plan_p0, p.q, p.k, p.v, out_p, p.scale, ws_p), 5, warmup=1)
@@ -538,9 +562,9 @@ def bench_mixed(w5, steps, warmup, with_padded=True):
 
 
 def cpu_baseline(p):
-    """The oracle as it stands, timed on every 8th query row (all heads) of the prefill part of the batch."""
+    """The oracle as it stands, timed on every 24th query row (all heads) of the prefill part of the batch."""
     from oracle import attention as oa
-    stride = 8
+    stride = 24
     rows = np.array([(i, h, t) for i in range(p.n) for t in range(0, int(p.q_lens[i]), stride)
                      for h in range(p.Hq)], dtype=np.int32)
     ctx = (p.kv_lens - p.q_lens).astype(np.int64)

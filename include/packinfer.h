@@ -238,6 +238,31 @@ int pk_packed_decode_attn(pk_plan* plan, const void* q, const void* kv_buf,
                           int dtype, int out_dtype,
                           void* workspace, size_t workspace_bytes, void* stream);
 
+/* ------------------------------------------------------------------------
+ * pk_packed_mixed_step -- Sec. 3 (overview): the prefill and the decode
+ * requests of one continuous-batching step go through the same packed
+ * execution.  One call for both halves of such a step: the packed prefill
+ * tiles of `prefill_plan` and the packed decode work items of `decode_plan`
+ * run in ONE launch in which workgroups of the two kinds alternate, so that
+ * the HBM-bound decode work runs beside the matrix-bound prefill work on the
+ * same compute units; the LSE merge of the decode partials follows as a
+ * second launch.  Results are those of pk_packed_prefill_attn and
+ * pk_packed_decode_attn (same arithmetic per tile and per work item).
+ *   prefill half: prefill_plan, q, k, v, out, prefill_workspace (as for
+ *                 pk_packed_prefill_attn)
+ *   decode half:  decode_plan (q_lens == 1), decode_q, kv_buf (written by
+ *                 pk_kv_reorganize), decode_out, decode_workspace (as for
+ *                 pk_packed_decode_attn); the workspaces must differ
+ *   scale, Hq, Hkv, d, dtype, out_dtype: common to both halves (one layer)
+ * A plan with n = 0 makes the call equal to the other half's own call.
+ * Errors: as for the two calls; PK_EUNSUPPORTED unless dtype is PK_BF16 and
+ * d = 128. */
+int pk_packed_mixed_step(pk_plan* prefill_plan, const void* q, const void* k, const void* v, void* out,
+                         void* prefill_workspace, size_t prefill_workspace_bytes,
+                         pk_plan* decode_plan, const void* decode_q, const void* kv_buf, void* decode_out,
+                         void* decode_workspace, size_t decode_workspace_bytes,
+                         float scale, int Hq, int Hkv, int d, int dtype, int out_dtype, void* stream);
+
 /* pk_packed_decode_attn_static -- pk_packed_decode_attn for callers that
  * cannot allocate device memory: code under HIP graph capture, tight serving
  * loops, harnesses that forbid hipMalloc.  It takes no workspace: the plan's

@@ -64,6 +64,8 @@ def lib():
         getattr(L, name).argtypes = [vp, vp, vp, vp, vp, f32, ci, ci, ci, ci, ci, vp, sz, vp]
     L.pk_packed_decode_attn.restype = ci
     L.pk_packed_decode_attn.argtypes = [vp, vp, vp, vp, f32, ci, ci, ci, ci, ci, vp, sz, vp]
+    L.pk_packed_mixed_step.restype = ci
+    L.pk_packed_mixed_step.argtypes = [vp, vp, vp, vp, vp, vp, sz, vp, vp, vp, vp, vp, sz, f32, ci, ci, ci, ci, ci, vp]
     L.pk_packed_decode_attn_static.restype = ci
     L.pk_packed_decode_attn_static.argtypes = [vp, vp, vp, vp, f32, ci, ci, ci, ci, ci, vp]
     L.pk_padded_decode_attn.restype = ci
@@ -98,6 +100,7 @@ EXPORTS = [
     "pk_padded_prefill_attn", "pk_padded_decode_attn", "pk_plan_stat", "pk_last_error",
     "pk_kv_append", "pk_packed_decode_attn_grown", "pk_regroup_due", "pk_trie_partition",
     "pk_pack_plan_tree", "pk_trie_tree", "pk_plan_tune", "pk_packed_decode_attn_static",
+    "pk_packed_mixed_step",
 ]
 STATIC_SCRATCH_BYTES = 16 << 20
 TUNE_DECODE_SPLIT = 0
@@ -303,6 +306,23 @@ def packed_decode_attn(plan, q, kv_buf, out, scale, Hkv, workspace, stream=None)
     _check(rc, "pk_packed_decode_attn")
     plan._ws = workspace
     return out
+
+
+def packed_mixed_step(prefill_plan, q, k, v, out, prefill_workspace,
+                      decode_plan, decode_q, kv_buf, decode_out, decode_workspace, scale, stream=None):
+    """Prefill tiles and decode work items of one continuous-batching step in one launch."""
+    _, Hq, d = q.shape
+    Hkv = k.shape[1]
+    rc = lib().pk_packed_mixed_step(
+        prefill_plan.handle, _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(prefill_workspace),
+        prefill_workspace.numel() * prefill_workspace.element_size(),
+        decode_plan.handle, _ptr(decode_q), _ptr(kv_buf), _ptr(decode_out), _ptr(decode_workspace),
+        decode_workspace.numel() * decode_workspace.element_size(),
+        float(scale), Hq, Hkv, d, _dtype_code(q), _dtype_code(out), _stream(stream))
+    _check(rc, "pk_packed_mixed_step")
+    prefill_plan._ws = prefill_workspace
+    decode_plan._ws = decode_workspace
+    return out, decode_out
 
 
 def packed_decode_attn_static(plan, q, kv_buf, out, scale, Hkv, stream=None):

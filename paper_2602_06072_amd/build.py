@@ -13,7 +13,7 @@ OBJ = os.path.join(CSRC, "_build")
 LIB = os.path.join(HERE, "libpackinfer.so")
 
 SOURCES = ["planner.cpp", "schedule.cpp", "api.cpp", "trie.cpp", "debug_f32.hip", "reorg.hip",
-           "decode.hip", "prefill.hip", "prefill_pipe.hip", "padded_decode.hip"]
+           "decode.hip", "prefill.hip", "prefill_pipe.hip", "padded_decode.hip", "mixed_step.hip"]
 
 HIP_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
              "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

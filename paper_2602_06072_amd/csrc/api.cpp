@@ -241,10 +241,12 @@ extern "C" int pk_kv_reorganize(pk_plan* plan, const void* k_pages, const void* 
     });
 }
 
+// args_out != nullptr: validate, bind and fill the kernel arguments, but launch nothing (the fused step)
 static int prefill_common(pk_plan* plan, const void* q, const void* k, const void* v, void* out,
                           float scale, int Hq, int Hkv, int d, int dtype, int out_dtype,
-                          void* workspace, size_t workspace_bytes, void* stream, bool padded) {
-    const char* who = padded ? "pk_padded_prefill_attn" : "pk_packed_prefill_attn";
+                          void* workspace, size_t workspace_bytes, void* stream, bool padded,
+                          PrefillArgs* args_out = nullptr, const char* who_override = nullptr) {
+    const char* who = who_override ? who_override : padded ? "pk_padded_prefill_attn" : "pk_packed_prefill_attn";
     std::string why;
     if (!plan) return fail(PK_EINVAL, std::string(who) + ": plan is NULL");
     if (plan->n == 0) return PK_OK;
@@ -275,6 +277,7 @@ static int prefill_common(pk_plan* plan, const void* q, const void* k, const voi
     a.total_q_rows = tq; a.total_kv_rows = tkv;
     a.Hq = Hq; a.Hkv = Hkv; a.d = d; a.scale = scale; a.out_f32 = out_dtype == PK_F32;
     a.xcd_swizzle = 1;             // both schedules: the r heads of a KV head share an XCD (and its L2)
+    if (args_out) { *args_out = a; return PK_OK; }
     const int e = dtype == PK_BF16 ? launch_prefill_bf16(a, stream) : launch_prefill_f32(a, stream);
     return e ? hip_fail(who, e) : PK_OK;
 }
@@ -302,7 +305,8 @@ namespace {
 int decode_common(const char* who, pk_plan* plan, const void* q, const void* kv_buf,
                   void* out, float scale, int32_t grown, int Hq, int Hkv, int d,
                   int dtype, int out_dtype,
-                  void* workspace, size_t workspace_bytes, void* stream, bool fixed_scratch = false) {
+                  void* workspace, size_t workspace_bytes, void* stream, bool fixed_scratch = false,
+                  DecodeArgs* args_out = nullptr) {
     const std::string w(who);
     std::string why;
     if (!plan) return fail(PK_EINVAL, w + ": plan is NULL");
@@ -338,6 +342,7 @@ int decode_common(const char* who, pk_plan* plan, const void* q, const void* kv_
     a.Hq = Hq; a.Hkv = Hkv; a.d = d; a.scale = scale; a.out_f32 = out_dtype == PK_F32;
     a.grown = grown;
     a.max_parts = t.dec_max_parts;
+    if (args_out) { *args_out = a; return PK_OK; }
     const int e = dtype == PK_BF16 ? launch_decode_bf16(a, stream) : launch_decode_f32(a, stream);
     return e ? hip_fail(who, e) : PK_OK;
 }
@@ -360,6 +365,39 @@ extern "C" int pk_packed_decode_attn_static(pk_plan* plan, const void* q, const 
     return pk::guarded<int>(PK_ENOMEM, PK_EINVAL, "pk_packed_decode_attn_static", [&]() -> int {
         return decode_common("pk_packed_decode_attn_static", plan, q, kv_buf, out, scale, 0, Hq, Hkv, d, dtype, out_dtype,
                              nullptr, 0, stream, true);
+    });
+}
+
+extern "C" int pk_packed_mixed_step(pk_plan* prefill_plan, const void* q, const void* k, const void* v, void* out,
+                                    void* prefill_workspace, size_t prefill_workspace_bytes,
+                                    pk_plan* decode_plan, const void* decode_q, const void* kv_buf, void* decode_out,
+                                    void* decode_workspace, size_t decode_workspace_bytes,
+                                    float scale, int Hq, int Hkv, int d, int dtype, int out_dtype, void* stream) {
+    return pk::guarded<int>(PK_ENOMEM, PK_EINVAL, "pk_packed_mixed_step", [&]() -> int {
+        const char* who = "pk_packed_mixed_step";
+        if (!prefill_plan || !decode_plan) return fail(PK_EINVAL, "pk_packed_mixed_step: plan is NULL");
+        if (dtype != PK_BF16 || d != 128)
+            return fail(PK_EUNSUPPORTED, "pk_packed_mixed_step: the fused launch is built for bf16 and d = 128 "
+                                         "(call pk_packed_prefill_attn and pk_packed_decode_attn otherwise)");
+        if (prefill_workspace && prefill_workspace == decode_workspace)
+            return fail(PK_EINVAL, "pk_packed_mixed_step: the two plans need a workspace each");
+        // either half may be empty: the other call does the whole step then
+        if (prefill_plan->n == 0)
+            return decode_common(who, decode_plan, decode_q, kv_buf, decode_out, scale, 0, Hq, Hkv, d, dtype, out_dtype,
+                                 decode_workspace, decode_workspace_bytes, stream);
+        if (decode_plan->n == 0)
+            return prefill_common(prefill_plan, q, k, v, out, scale, Hq, Hkv, d, dtype, out_dtype, prefill_workspace,
+                                  prefill_workspace_bytes, stream, false, nullptr, who);
+        PrefillArgs pa{};
+        DecodeArgs da{};
+        int rc = prefill_common(prefill_plan, q, k, v, out, scale, Hq, Hkv, d, dtype, out_dtype, prefill_workspace,
+                                prefill_workspace_bytes, stream, false, &pa, who);
+        if (rc != PK_OK) return rc;
+        rc = decode_common(who, decode_plan, decode_q, kv_buf, decode_out, scale, 0, Hq, Hkv, d, dtype, out_dtype,
+                           decode_workspace, decode_workspace_bytes, stream, false, &da);
+        if (rc != PK_OK) return rc;
+        const int e = launch_mixed_step_bf16(pa, da, stream);
+        return e ? hip_fail(who, e) : PK_OK;
     });
 }
 

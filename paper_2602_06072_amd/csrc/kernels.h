@@ -37,6 +37,7 @@ struct DecodeArgs {
     int32_t max_parts;                              // most partial results of one request
 };
 int launch_decode_bf16(const DecodeArgs& a, void* stream);
+int launch_decode_merge_bf16(const DecodeArgs& a, void* stream);   // the LSE merge alone
 // Device address of the library's fixed scratch array on the current device (looked up once per
 // device); returns a hipError_t as int.
 int static_scratch_address(void** ptr);
@@ -76,6 +77,8 @@ __device__ __forceinline__ void prefill_tile_row(const PrefillArgs& a, int tile,
 #endif
 int launch_prefill_bf16(const PrefillArgs& a, void* stream);
 int launch_prefill_f32(const PrefillArgs& a, void* stream);
+// prefill tiles and decode work items of one step in one launch (bf16, d = 128), then the LSE merge
+int launch_mixed_step_bf16(const PrefillArgs& pa, const DecodeArgs& da, void* stream);
 
 struct PagedDecodeArgs {
     const void* q; const void* k_pages; const void* v_pages; void* out;

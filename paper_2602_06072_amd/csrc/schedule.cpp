@@ -326,8 +326,14 @@ void emit_sched(const SchedBuild& sb, const std::vector<int32_t>& order, Builder
 
 // packed: tiles over each group's packed row stream, heaviest tile first
 void build_prefill_packed(const pk_plan& plan, const std::vector<int64_t>& q_start,
-                          const std::vector<int64_t>& kv_start, Builder& b, DeviceTables& t) {
+                          const std::vector<int64_t>& kv_start, int Hq, int num_cus, Builder& b, DeviceTables& t) {
     constexpr int BM = kPrefillBM;
+    // A batch so small that even one tile per request piece leaves workgroup slots empty (two per
+    // compute unit) gains nothing from sharing tiles between requests: a shared tile walks the key
+    // tiles of both requests one after the other, which only lengthens the longest workgroup.
+    int64_t aligned_tiles = 0;
+    for (int32_t i = 0; i < plan.n; ++i) aligned_tiles += (plan.q_lens[i] + BM - 1) / BM;
+    const bool may_share = aligned_tiles * Hq > 2 * static_cast<int64_t>(num_cus);
     SchedBuild sb;
     std::vector<QRow> rows;
     std::vector<int32_t> tile_req;                 // request of a tile's first row
@@ -341,9 +347,9 @@ void build_prefill_packed(const pk_plan& plan, const std::vector<int64_t>& q_sta
             // tile walks the key tiles of both requests one after the other and runs them masked.
             const int32_t lq = plan.q_lens[m.req];
             const int32_t room = BM - static_cast<int32_t>(rows.size());
-            if (!rows.empty() && lq > room) {
+            if (!rows.empty() && (lq > room || !may_share)) {
                 const int32_t last = lq % BM == 0 ? BM : lq % BM;   // rows of its last tile when it starts fresh
-                if (room < last) {
+                if (room < last || !may_share) {
                     tile_req.push_back(rows[0].req);
                     add_tile(plan, q_start, kv_start, rows.data(), static_cast<int>(rows.size()), false, sb);
                     rows.clear();
@@ -453,18 +459,20 @@ void build_tables(const pk_plan& plan, int Hq, int Hkv, int d, int dtype, int nu
     t.kv_start = b.add(std::vector<int32_t>(kv_start.begin(), kv_start.end()));
     build_reorg(plan, b, t);
     if (plan.decode_only) build_decode(plan, Hq, Hkv, num_cus, b, t);
-    build_prefill_packed(plan, q_start, kv_start, b, t);
+    build_prefill_packed(plan, q_start, kv_start, Hq, num_cus, b, t);
     t.host.resize((t.host.size() + 63) / 64 * 64, 0);
     t.tables_bytes = t.host.size() * sizeof(int32_t);
     t.partial_offset = t.tables_bytes;
     t.partial_bytes = static_cast<size_t>(t.n_dec_parts) * Hq * (static_cast<size_t>(d) + 1) * sizeof(float);
     t.decode_only_bytes = t.partial_offset + t.partial_bytes;
     if (plan.decode_only) {
-        // the padded comparison kernel keeps (request, split) partials in the same region: at most
-        // 16 splits, each a multiple of 32 tokens and at least 256 tokens long
+        // the padded comparison kernel keeps (request, split) partials in the same region: the
+        // same number of splits for every request, sized by the longest -- at most 64, each a
+        // multiple of 32 tokens and at least 512 tokens long (enough waves to fill the chip from the
+        // long requests alone; more splits only add empty grid slots and partial results)
         int32_t max_len = 0;
         for (int32_t L : plan.kv_lens) max_len = std::max(max_len, L);
-        int32_t split = std::max(256, ((max_len + 15) / 16 + 31) / 32 * 32);
+        int32_t split = std::max(512, ((max_len + 63) / 64 + 31) / 32 * 32);
         t.pad_split_tokens = split;
         t.pad_n_splits = (max_len + split - 1) / split;
         const size_t pad_bytes = static_cast<size_t>(plan.n) * t.pad_n_splits * Hq * (static_cast<size_t>(d) + 1) * sizeof(float);

@@ -19,7 +19,7 @@ def test_prefill_key_list_longer_than_the_skip_counters():
     # of request 0: more than the 255 their skip counter can say.  Request 2 starts a fresh tile
     # (the layout follows Alg. 1's order, longest first, so the second longest request comes second).
     kv = np.asarray([16448, 64, 40], dtype=np.int32)
-    w = wl.make_ragged("long_list", kv, kv, 2, 1, 128, 1 << 20, 3, DEV)
+    w = wl.make_ragged("long_list", kv, kv, 4, 1, 128, 1 << 20, 3, DEV)     # 131 x 4 workgroups: enough for tiles to be shared
     plan = pk.pack_plan(w.kv_lens, w.q_lens, token_budget=w.token_budget)
     ws = pk.new_workspace(plan, w.Hq, w.Hkv, w.d, pk.PK_BF16)
     pk.plan_bind(plan, w.Hq, w.Hkv, w.d, pk.PK_BF16, ws)
