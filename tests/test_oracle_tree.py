@@ -193,3 +193,61 @@ def test_tree_group_buffer_rebuilds_every_request():
         assert np.array_equal(np.concatenate(parts), logical[req])
     # headroom rows stay untouched
     assert np.isnan(buf).any() and np.isnan(buf).reshape(g.buf_tokens, -1).all(axis=1).sum() == 2 * len(kv)
+
+
+def brute_force_tree(seqs, min_prefix):
+    """The prefix tree straight from its definition, without walking a tree: a node is a pair
+    (M, D) where D is the length of the common prefix of two requests (a point where they branch,
+    or where one of them ends) and M is the set of ALL requests that start with those D tokens;
+    D >= min_prefix.  The parent of a node is the node with the deepest D' < D whose set contains
+    M; a node's segment is the tokens [D', D); a request hangs below the deepest node that holds it;
+    nodes are numbered by (lowest request, depth)."""
+    n = len(seqs)
+    nodes = set()
+    for i in range(n):
+        for j in range(i + 1, n):
+            D = 0
+            while D < min(len(seqs[i]), len(seqs[j])) and seqs[i][D] == seqs[j][D]:
+                D += 1
+            if D < min_prefix:
+                continue
+            M = frozenset(k for k in range(n) if len(seqs[k]) >= D and list(seqs[k][:D]) == list(seqs[i][:D]))
+            nodes.add((min(M), D, M))
+    order = sorted(nodes, key=lambda x: (x[0], x[1]))
+    parent, length, saved = [], [], 0
+    for (lo, D, M) in order:
+        best = -1
+        for k, (lo2, D2, M2) in enumerate(order):
+            if D2 < D and M <= M2 and (best < 0 or D2 > order[best][1]):
+                best = k
+        parent.append(best)
+        length.append(D - (order[best][1] if best >= 0 else 0))
+        saved += length[-1] * (len(M) - 1)
+    req_node = []
+    for i in range(n):
+        best = -1
+        for k, (lo, D, M) in enumerate(order):
+            if i in M and (best < 0 or D > order[best][1]):
+                best = k
+        req_node.append(best)
+    return parent, length, req_node, saved
+
+
+def test_whole_tree_hand_case_with_a_request_that_ends_at_a_node():
+    # A ends exactly where B and C branch; D shares only the first token with them
+    seqs = [[1, 2], [1, 2, 3], [1, 2, 4, 4], [1, 9]]
+    parent, length, req_node, saved = trie.trie_tree(seqs, 1)
+    assert parent == [-1, 0] and length == [1, 1]           # node 0: [1] over all four; node 1: [2] over A, B, C
+    assert req_node == [1, 1, 1, 0]
+    assert saved == 1 * 3 + 1 * 2
+    assert (parent, length, req_node, saved) == brute_force_tree(seqs, 1)
+    # with min_prefix 2 the outer node disappears and the inner one carries both tokens
+    assert trie.trie_tree(seqs, 2) == ([-1], [2], [0, 0, 0, -1], 4) == brute_force_tree(seqs, 2)
+
+
+@settings(max_examples=500, deadline=None)
+@given(st.lists(st.lists(st.integers(0, 2), min_size=1, max_size=7), min_size=0, max_size=7), st.integers(1, 3))
+def test_whole_tree_equals_the_definition_enumerated(seqs, mp):
+    # complete node set, parents, segment lengths, attachment of every request (also of requests
+    # that end exactly at a node, and of duplicates) and the saving
+    assert tuple(trie.trie_tree(seqs, mp)) == tuple(brute_force_tree(seqs, mp))
