@@ -680,6 +680,12 @@ def main():
                               "kernel": "reorg_bf16_kernel<128>", "kernel_ms": m["relayout_ms"],
                               "bytes_per_launch": m["relayout_alg_bytes"]},
     }
+    line["fused_step"] = {
+        "what": "the same step with prefill tiles and decode work items in ONE launch (pk_packed_mixed_step), timed in a "
+                "second loop of the same length",
+        "ms_per_step": m["fused_ms_per_step"], "value": m["fused_step_tflops"], "unit": "TFLOP/s",
+        "fused_prefill_plus_decode_ms": m["fused_prefill_plus_decode_ms"],
+        "separate_prefill_plus_decode_ms": m["separate_prefill_plus_decode_ms"]}
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline(w5.prefill)
     extra = {"mixed_cfg5": m}
