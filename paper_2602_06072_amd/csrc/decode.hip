@@ -23,7 +23,7 @@ namespace {
 // Work items with at most 16 query rows: one column tile, tile loads double buffered.
 template <int D>
 __global__ __launch_bounds__(64) void decode_bf16_kernel(DecodeArgs a) {
-    decode_body<D, 1, true>(a, blockIdx.x, blockIdx.y);
+    decode_body<D, 1, 1>(a, blockIdx.x, blockIdx.y);
 }
 
 // Batches with shared prefixes: the first n_wide work items carry 17..32 query rows (two column
@@ -31,8 +31,8 @@ __global__ __launch_bounds__(64) void decode_bf16_kernel(DecodeArgs a) {
 // the chip together; occupancy, not register prefetch, hides the load latency here.
 template <int D>
 __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void decode_bf16_mixed_kernel(DecodeArgs a) {
-    if (static_cast<int>(blockIdx.x) < a.n_wide) decode_body<D, 2, false>(a, blockIdx.x, blockIdx.y);
-    else decode_body<D, 1, false>(a, blockIdx.x, blockIdx.y);
+    if (static_cast<int>(blockIdx.x) < a.n_wide) decode_body<D, 2, 2>(a, blockIdx.x, blockIdx.y);
+    else decode_body<D, 1, 2>(a, blockIdx.x, blockIdx.y);
 }
 
 // out[i, h, :] = sum_j exp(lse_j - lse) o_j over the request's partial slots (consecutive).

@@ -7,7 +7,12 @@
 namespace pk {
 namespace {
 
-template <int D, int NT, bool PREFETCH>
+// PREFETCH: 0 = one tile at a time; 1 = two register sets (the loads of tile b+1 are in flight while
+// tile b is processed); 2 = one register set, rolling: the K part of tile b+1 is requested as soon as
+// the scores of tile b are done and its V part as soon as P.V of tile b is done, so that each half of
+// the next tile is in flight under the other half's arithmetic without a second set of registers
+// (for work items with two column tiles of query rows, which have no registers to spare).
+template <int D, int NT, int PREFETCH>
 __device__ __forceinline__ void decode_body(const DecodeArgs& a, const int item, const int kvh) {
     constexpr int KS = D / 32;                 // K steps per 16-key sub-tile
     constexpr int VT = D / 16;                 // V column blocks
@@ -63,58 +68,87 @@ __device__ __forceinline__ void decode_body(const DecodeArgs& a, const int item,
     }
     const float sl2 = a.scale * kLog2e;
 
-    auto process = [&](const u32x4 (&kraw)[NK], const u32x4 (&vraw)[VT], int b) {
+    // scores and probabilities of tile b for column tile c: leaves P (bf16, B operand) and the
+    // factor alpha for what has been accumulated so far
+    auto scores = [&](const u32x4 (&kraw)[NK], int b, int c, bf16x8& pf, float& alpha) {
         const bool edge = (b * 32 < tok_begin) || (b * 32 + 32 > tok_end);
+        floatx4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kraw[s]), qf[c][s], s0, 0, 0, 0);
+            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kraw[KS + s]), qf[c][s], s1, 0, 0, 0);
+        }
+        // lane (n, g) now holds scores of row n against keys 32b + 16u + 4g + j
+        float x[8];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { x[j] = s0[j] * sl2; x[4 + j] = s1[j] * sl2; }
+        if (edge) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int key = b * 32 + (j < 4 ? 4 * g + j : 16 + 4 * g + (j - 4));
+                if (key < tok_begin || key >= tok_end) x[j] = -INFINITY;
+            }
+        }
+        float mx = x[0];
+#pragma unroll
+        for (int j = 1; j < 8; ++j) mx = fmaxf(mx, x[j]);
+        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_new = fmaxf(m[c], mx);
+        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+        alpha = __builtin_amdgcn_exp2f(m[c] - m_use);      // 0 on the first tile
+        float ps = 0.f;
+        uint32_t pw[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            floatx2 pp;
+            pp[0] = __builtin_amdgcn_exp2f(x[2 * j] - m_use);
+            pp[1] = __builtin_amdgcn_exp2f(x[2 * j + 1] - m_use);
+            ps += pp[0] + pp[1];
+            pw[j] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pp, bf16x2));
+        }
+        l[c] = l[c] * alpha + ps;
+        m[c] = m_new;
+        pf = __builtin_bit_cast(bf16x8, u32x4{pw[0], pw[1], pw[2], pw[3]});
+    };
+    auto pv = [&](const u32x4 (&vraw)[VT], int c, const bf16x8& pf, float alpha) {
+#pragma unroll
+        for (int t = 0; t < VT; ++t) {
+            floatx4 acc = o[c][t];
+            acc[0] *= alpha; acc[1] *= alpha; acc[2] *= alpha; acc[3] *= alpha;
+            o[c][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vraw[t]), pf, acc, 0, 0, 0);
+        }
+    };
+    auto process = [&](const u32x4 (&kraw)[NK], const u32x4 (&vraw)[VT], int b) {
 #pragma unroll
         for (int c = 0; c < NT; ++c) {
-            floatx4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int s = 0; s < KS; ++s) {
-                s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kraw[s]), qf[c][s], s0, 0, 0, 0);
-                s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kraw[KS + s]), qf[c][s], s1, 0, 0, 0);
-            }
-            // lane (n, g) now holds scores of row n against keys 32b + 16u + 4g + j
-            float x[8];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) { x[j] = s0[j] * sl2; x[4 + j] = s1[j] * sl2; }
-            if (edge) {
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const int key = b * 32 + (j < 4 ? 4 * g + j : 16 + 4 * g + (j - 4));
-                    if (key < tok_begin || key >= tok_end) x[j] = -INFINITY;
-                }
-            }
-            float mx = x[0];
-#pragma unroll
-            for (int j = 1; j < 8; ++j) mx = fmaxf(mx, x[j]);
-            mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            const float m_new = fmaxf(m[c], mx);
-            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-            const float alpha = __builtin_amdgcn_exp2f(m[c] - m_use);      // 0 on the first tile
-            float ps = 0.f;
-            uint32_t pw[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                floatx2 pp;
-                pp[0] = __builtin_amdgcn_exp2f(x[2 * j] - m_use);
-                pp[1] = __builtin_amdgcn_exp2f(x[2 * j + 1] - m_use);
-                ps += pp[0] + pp[1];
-                pw[j] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pp, bf16x2));
-            }
-            l[c] = l[c] * alpha + ps;
-            m[c] = m_new;
-            const bf16x8 pf = __builtin_bit_cast(bf16x8, u32x4{pw[0], pw[1], pw[2], pw[3]});
-#pragma unroll
-            for (int t = 0; t < VT; ++t) {
-                floatx4 acc = o[c][t];
-                acc[0] *= alpha; acc[1] *= alpha; acc[2] *= alpha; acc[3] *= alpha;
-                o[c][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vraw[t]), pf, acc, 0, 0, 0);
-            }
+            bf16x8 pf;
+            float alpha;
+            scores(kraw, b, c, pf, alpha);
+            pv(vraw, c, pf, alpha);
         }
     };
 
-    if (PREFETCH) {
+    if (PREFETCH == 2) {
+        for (int b = b0; b < b1; ++b) {
+            bf16x8 pf[NT];
+            float alpha[NT];
+#pragma unroll
+            for (int c = 0; c < NT; ++c) scores(ka, b, c, pf[c], alpha[c]);
+            if (b + 1 < b1) {                       // K registers are free: the next tile's K part
+                const u32x4* tile_ = base + static_cast<int64_t>(b + 1) * TILE_U4;
+#pragma unroll
+                for (int i = 0; i < NK; ++i) ka[i] = __builtin_nontemporal_load(tile_ + i * 64);
+            }
+#pragma unroll
+            for (int c = 0; c < NT; ++c) pv(va, c, pf[c], alpha[c]);
+            if (b + 1 < b1) {                       // V registers are free: the next tile's V part
+                const u32x4* tile_ = base + static_cast<int64_t>(b + 1) * TILE_U4;
+#pragma unroll
+                for (int i = 0; i < VT; ++i) va[i] = __builtin_nontemporal_load(tile_ + (NK + i) * 64);
+            }
+        }
+    } else if (PREFETCH == 1) {
         for (int b = b0; b < b1; b += 2) {
             if (b + 1 < b1) PK_LOAD_TILE(kb_, vb_, b + 1);
             process(ka, va, b);

@@ -32,8 +32,8 @@ __global__ __launch_bounds__(256, 2) void mixed_step_kernel(PrefillArgs pa, Deco
             const int unit = ((grp * kRun + pos - kRun) * 4) + static_cast<int>(threadIdx.x >> 6);
             const int item = unit / da.Hkv, kvh = unit % da.Hkv;
             if (item >= da.n_items) return;
-            if (item < da.n_wide) decode_body<128, 2, false>(da, item, kvh);
-            else decode_body<128, 1, true>(da, item, kvh);
+            if (item < da.n_wide) decode_body<128, 2, 2>(da, item, kvh);
+            else decode_body<128, 1, 1>(da, item, kvh);
             return;
         }
         prefill_block = grp * kRun + pos;

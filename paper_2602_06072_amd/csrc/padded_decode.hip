@@ -39,14 +39,11 @@ __global__ __launch_bounds__(64) void padded_decode_kernel(PagedDecodeArgs a) {
     const u32x4* kp = static_cast<const u32x4*>(a.k_pages);
     const u32x4* vp = static_cast<const u32x4*>(a.v_pages);
 
-    // page sizes are powers of two in practice: a shift and a mask instead of a division per row
-    const int shift = (a.page_size & (a.page_size - 1)) == 0 ? __builtin_ctz(a.page_size) : -1;
     auto token_row = [&](int tok) -> int64_t {      // row of a logical token in the pool (clamped)
         const int tc = tok < len ? tok : len - 1;
-        const int lp = shift >= 0 ? tc >> shift : tc / a.page_size;
-        int64_t page = bt[lp];
+        int64_t page = bt[tc / a.page_size];
         page = page < 0 ? 0 : (page >= a.num_blocks ? a.num_blocks - 1 : page);
-        return page * a.page_size + (tc - lp * a.page_size);
+        return page * a.page_size + tc % a.page_size;
     };
     // Raw loads of the tile that starts at token t0.  K operand of sub-tile u: lane (n, g) reads 16
     // bytes of token t0 + 16u + n; V: the 32 rows as coalesced 16-byte chunks.

@@ -103,16 +103,26 @@ __device__ __forceinline__ bool setup(const PrefillArgs& a, const int block, Wor
         const int row = 16 * u.wave + 4 * q + r_in;
         off.g[q] = static_cast<int>(row * u.row_bytes + u.kvh * ROWB + ((pos ^ swz(row)) << 4));
     }
-    // Q operand: lane (n, hlf) holds Q[row n][16s + 8hlf .. +8], multiplied by scale * log2(e) in
-    // fp32 and rounded to bf16 again: the MFMAs then deliver the scores in the exp2 domain and the
-    // softmax needs no multiplication per score.
+    // Q operand: lane (n, hlf) holds Q[row n][16s + 8hlf .. +8].  Only requested here: the caller
+    // scales it (scale_q) after it has requested the first K/V tiles, so that the two round trips
+    // to memory overlap.
     const uint16_t* qp = static_cast<const uint16_t*>(a.q) +
                          (static_cast<int64_t>(u.qrow < 0 ? 0 : u.qrow) * a.Hq + u.head) * D + 8 * u.hlf;
-    const float sl2 = a.scale * kLog2e;
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
         u32x4 raw = {0u, 0u, 0u, 0u};
         if (u.qrow >= 0) raw = *reinterpret_cast<const u32x4*>(qp + 16 * s);
+        qf[s] = __builtin_bit_cast(bf16x8, raw);
+    }
+    return true;
+}
+
+// Q times scale * log2(e), in fp32, rounded to bf16 again: the MFMAs then deliver the scores in the
+// exp2 domain and the softmax needs no multiplication per score.
+__device__ __forceinline__ void scale_q(bf16x8 (&qf)[KS], float sl2) {
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+        const u32x4 raw = __builtin_bit_cast(u32x4, qf[s]);
         u32x4 scaled;
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
@@ -123,7 +133,6 @@ __device__ __forceinline__ bool setup(const PrefillArgs& a, const int block, Wor
         }
         qf[s] = __builtin_bit_cast(bf16x8, scaled);
     }
-    return true;
 }
 
 // o / l to global memory; lane (n, hlf) owns columns 32b + 8q + 4hlf .. +3 of its query row.
@@ -434,6 +443,7 @@ __device__ __forceinline__ void prefill_tile_body(const PrefillArgs& a, const in
     PK_COPY_TILE(a.k, e0s, 0, true);
     PK_COPY_TILE(a.k, e1s, TILE_BYTES, 1 < n_kv);
     PK_COPY_TILE(a.v, e0s, 3 * TILE_BYTES, true);
+    scale_q(qf, a.scale * kLog2e);                 // (waits for the Q loads, which were requested first)
     PK_WAIT_ALL_COPIES();
     __syncthreads();
 
