@@ -593,6 +593,33 @@ def profiled(tag, field):
     return None
 
 
+def plain_kernel_rates(torch, dev):
+    """What plain library kernels reach on this GPU's HBM, for context next to the roofline fractions: an elementwise
+    kernel that reads 2 GiB and writes 2 GiB, a device-to-device copy of the same size, a fill of 2 GiB."""
+    n = 1 << 29
+    src = torch.ones(n, dtype=torch.int32, device=dev)
+    dst = torch.empty_like(src)
+
+    def best(fn, reps=5):
+        fn()
+        torch.cuda.synchronize()
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for a, b in ev:
+            a.record()
+            fn()
+            b.record()
+        torch.cuda.synchronize()
+        return min(a.elapsed_time(b) for a, b in ev)
+    out = {"what": "min of 5 launches over 2 GiB int32 tensors (bytes read + bytes written per ms)"}
+    for name, fn, nbytes in (("elementwise_add_gbs", lambda: torch.add(src, 1, out=dst), 8.0 * n),
+                             ("copy_gbs", lambda: dst.copy_(src), 8.0 * n),
+                             ("fill_gbs", lambda: dst.zero_(), 4.0 * n)):
+        out[name] = nbytes / best(fn) / 1e6
+    out["elementwise_add_frac_of_peak"] = out["elementwise_add_gbs"] / HBM_PEAK_GBS
+    del src, dst
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -680,6 +707,7 @@ def main():
                               "kernel": "reorg_bf16_kernel<128>", "kernel_ms": m["relayout_ms"],
                               "bytes_per_launch": m["relayout_alg_bytes"]},
     }
+    line["hbm_plain_kernels"] = plain_kernel_rates(torch, dev)
     line["fused_step"] = {
         "what": "the same step with prefill tiles and decode work items in ONE launch (pk_packed_mixed_step), timed in a "
                 "second loop of the same length",
