@@ -364,7 +364,25 @@ def capacity_sweep(wl, pk, seed, dev):
                         f"{tag}_partials": plan.stat(4), f"{tag}_decode_ms": ms})
             del buf, ws
         splits.append(row)
-    return {"capacity": rows, "decode_split": splits,
+    # the prefill pipeline (how K/V tiles reach LDS; same tile shape, same arithmetic), on configuration 2, on the
+    # prefill half of configuration 5, and on configuration 2's lengths with head dimension 64
+    pipes = []
+    w5p = wl.config5(seed, device=dev, decodes=4).prefill
+    w2d64 = wl.make_ragged("cfg2_lengths_d64", w2.kv_lens, w2.q_lens, 32, 8, 64, 16384, seed, dev)
+    for tag, w, reps in (("cfg2", w2, 20), ("cfg5_prefill", w5p, 5), ("cfg2_lengths_d64", w2d64, 20)):
+        row = {"workload": tag, "d": w.d}
+        o = torch.empty(w.q.shape, dtype=torch.bfloat16, device=dev)
+        for name, code in (("direct_to_lds", 0), ("register_staged", 1)):
+            plan = pk.pack_plan(w.kv_lens, w.q_lens, token_budget=w.token_budget)
+            plan.tune(pk.TUNE_PREFILL_PIPELINE, code)
+            ws = pk.new_workspace(plan, w.Hq, w.Hkv, w.d, pk.PK_BF16)
+            pk.plan_bind(plan, w.Hq, w.Hkv, w.d, pk.PK_BF16, ws)
+            ms, _ = _time_launches(lambda: pk.packed_prefill_attn(plan, w.q, w.k, w.v, o, w.scale, ws), reps)
+            row[name + "_ms"] = ms
+            row[name + "_tflops"] = prefill_flops(w, plan.stat(0)) / (ms * 1e-3) / 1e12
+            del ws
+        pipes.append(row)
+    return {"capacity": rows, "decode_split": splits, "prefill_pipeline": pipes,
             "prefill_tile_shape": "128 query rows x 64 keys per workgroup step (4 waves x 32 rows, two key halves of 32): "
                                   "fixed at compile time by the register budget of the MFMA scheme, not swept"}
 

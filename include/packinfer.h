@@ -410,10 +410,17 @@ int64_t pk_plan_stat(const pk_plan* plan, int what);
  * shapes are found by profiling a range of settings).  Overrides a choice of
  * the schedule builder for this plan; the next pk_workspace_bytes /
  * pk_plan_bind builds the tables again.  Results never depend on it.
- *   PK_TUNE_DECODE_SPLIT  tokens per split-KV work item (rounded up to
- *                         PK_KV_BLOCK); 0 = the builder's own choice
+ *   PK_TUNE_DECODE_SPLIT     tokens per split-KV work item (rounded up to
+ *                            PK_KV_BLOCK); 0 = the builder's own choice
+ *   PK_TUNE_PREFILL_PIPELINE how the bf16 prefill kernels (packed and padded)
+ *                            bring K/V tiles into LDS: 0 = copied straight
+ *                            from memory into LDS, three K and two V stages
+ *                            (default); 1 = staged through registers, two
+ *                            stages with padded rows.  Same tile shape (128
+ *                            query rows x 64 keys), same arithmetic.
  * Errors: PK_EINVAL (NULL plan, unknown knob, value out of range). */
 #define PK_TUNE_DECODE_SPLIT 0
+#define PK_TUNE_PREFILL_PIPELINE 1
 int pk_plan_tune(pk_plan* plan, int knob, int64_t value);
 
 /* Message of the last error on this thread ("" if none). */

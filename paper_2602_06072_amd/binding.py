@@ -104,6 +104,7 @@ EXPORTS = [
 ]
 STATIC_SCRATCH_BYTES = 16 << 20
 TUNE_DECODE_SPLIT = 0
+TUNE_PREFILL_PIPELINE = 1
 REGROUP_DRIFT, REGROUP_HEADROOM, REGROUP_DRIFT_WITHIN_BUDGET = 1, 2, 4
 
 

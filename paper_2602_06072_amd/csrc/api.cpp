@@ -277,6 +277,7 @@ static int prefill_common(pk_plan* plan, const void* q, const void* k, const voi
     a.total_q_rows = tq; a.total_kv_rows = tkv;
     a.Hq = Hq; a.Hkv = Hkv; a.d = d; a.scale = scale; a.out_f32 = out_dtype == PK_F32;
     a.xcd_swizzle = 1;             // both schedules: the r heads of a KV head share an XCD (and its L2)
+    a.pipeline = plan->tune_prefill_pipeline;
     if (args_out) { *args_out = a; return PK_OK; }
     const int e = dtype == PK_BF16 ? launch_prefill_bf16(a, stream) : launch_prefill_f32(a, stream);
     return e ? hip_fail(who, e) : PK_OK;
@@ -508,6 +509,11 @@ extern "C" int pk_padded_decode_attn(pk_plan* plan, const void* q,
 extern "C" int pk_plan_tune(pk_plan* plan, int knob, int64_t value) {
     return pk::guarded<int>(PK_ENOMEM, PK_EINVAL, "pk_plan_tune", [&]() -> int {
         if (!plan) return fail(PK_EINVAL, "pk_plan_tune: plan is NULL");
+        if (knob == PK_TUNE_PREFILL_PIPELINE) {
+            if (value != 0 && value != 1) return fail(PK_EINVAL, "pk_plan_tune: prefill pipeline must be 0 (direct to LDS) or 1 (staged through registers)");
+            plan->tune_prefill_pipeline = static_cast<int32_t>(value);
+            return PK_OK;                              // (read at every prefill call; the tables do not depend on it)
+        }
         if (knob != PK_TUNE_DECODE_SPLIT) return fail(PK_EINVAL, "pk_plan_tune: unknown knob");
         if (value < 0 || value > (1 << 20)) return fail(PK_EINVAL, "pk_plan_tune: decode split must be in [0, 2^20] tokens");
         plan->tune_decode_split = static_cast<int32_t>(value);

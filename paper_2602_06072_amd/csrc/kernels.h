@@ -52,6 +52,7 @@ struct PrefillArgs {
     int64_t total_q_rows; int64_t total_kv_rows;
     int Hq; int Hkv; int d; float scale; int out_f32;
     int xcd_swizzle;                                // 1: place the heads of a KV head on one XCD
+    int pipeline;                                   // 0: K/V tiles copied straight into LDS; 1: staged through registers
 };
 #if defined(__HIPCC__)
 // Row `local` (0..127) of query tile `tile`: its Q row (-1: padding) and its key range [lo, hi).

@@ -10,7 +10,11 @@
 // the heads of a KV head still share an L2.  The LSE merge of the decode partials is a
 // second, short launch.
 #include "decode_body.hip.h"
+#define PK_D 128
+#define PK_DNS d128
 #include "prefill_body.hip.h"
+#undef PK_D
+#undef PK_DNS
 
 namespace pk {
 namespace {
@@ -22,7 +26,7 @@ constexpr int kRun = 256;
 
 __global__ __launch_bounds__(256, 2) void mixed_step_kernel(PrefillArgs pa, DecodeArgs da, int n_prefill_blocks,
                                                             int n_decode_blocks) {
-    __shared__ __align__(1024) unsigned char lds[5 * TILE_BYTES];
+    __shared__ __align__(1024) unsigned char lds[5 * d128::TILE_BYTES];
     const int x = static_cast<int>(blockIdx.x);
     const int decode_groups = (n_decode_blocks + kRun - 1) / kRun;
     int prefill_block;
@@ -41,7 +45,7 @@ __global__ __launch_bounds__(256, 2) void mixed_step_kernel(PrefillArgs pa, Deco
         prefill_block = x - decode_groups * kRun;
     }
     if (prefill_block >= n_prefill_blocks) return;
-    prefill_tile_body(pa, prefill_block, lds);
+    d128::prefill_tile_body(pa, prefill_block, lds);
 }
 
 }  // namespace

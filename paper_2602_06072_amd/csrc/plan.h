@@ -104,6 +104,7 @@ struct pk_plan {
     int64_t unmasked_pairs = 0;
     std::vector<int32_t> words;     // canonical serialisation
     int32_t tune_decode_split = 0;  // pk_plan_tune: 0 = chosen by the schedule builder
+    int32_t tune_prefill_pipeline = 0;   // 1: the register-staged prefill kernel (pk_plan_tune)
     // binding state: a cache of what was last built / uploaded for this plan, also filled by the
     // size query on a const plan (calls on one plan are serialised by the caller)
     mutable pk::DeviceTables tables;

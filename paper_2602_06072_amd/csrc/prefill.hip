@@ -13,8 +13,9 @@
 // operand layout of the second.  K/V tiles are staged through LDS (double
 // buffered, one barrier per tile); global loads of tile j+1 are issued before
 // the math of tile j.  MFMA-bound: 4*D flops per (query, key) pair.
-// This staged kernel serves head dimension 64; head dimension 128 runs the
-// direct-to-LDS kernel of prefill_pipe.hip (same tables, same arithmetic).
+// This register-staged kernel is the second pipeline (pk_plan_tune, PK_TUNE_PREFILL_PIPELINE = 1);
+// by default both head dimensions run the direct-to-LDS kernels of prefill_pipe.hip (same tables,
+// same tile shape, same arithmetic).
 
 #include <mutex>
 
@@ -315,7 +316,8 @@ int launch_prefill_bf16_pipe(const PrefillArgs& a, void* stream);
 
 int launch_prefill_bf16(const PrefillArgs& a, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (a.d == 128) return launch_prefill_bf16_pipe(a, stream);   // direct-to-LDS kernel (prefill_pipe.hip)
+    if (a.pipeline == 0) return launch_prefill_bf16_pipe(a, stream);   // direct-to-LDS kernels (prefill_pipe.hip)
+    if (a.d == 128) return launch_p<128>(a, st);                       // the register-staged kernel of this file
     if (a.d == 64) return launch_p<64>(a, st);
     return static_cast<int>(hipErrorInvalidValue);
 }

@@ -1,4 +1,4 @@
-// Packed prefill attention, bf16 MFMA, head dimension 128 (Sec. 3.1).  Same tables, same
+// Packed prefill attention, bf16 MFMA, head dimension PK_D = 128 or 64 (Sec. 3.1).  Same tables, same
 // arithmetic and same operand scheme as prefill.hip (S^T = K.Q^T, O^T += V^T.P^T with
 // v_mfma_f32_32x32x16_bf16, one wave per 32 query rows, key tiles of 64), but
 //   * K/V tiles go HBM/L2 -> LDS directly (buffer_load ... lds, 16 bytes per lane, no staging
@@ -13,38 +13,61 @@
 //   * copies are requested one tile ahead for V and two for K; one barrier per tile.
 
 // Device code only: included by prefill_pipe.hip (the prefill launch) and by mixed_step.hip (the
-// fused prefill + decode launch).
-#pragma once
+// fused prefill + decode launch).  The includer defines PK_D (the head dimension) and PK_DNS (the
+// namespace this instance goes into) first; the file may be included once per head dimension.
+// With PK_D = 64 a row is 128 bytes, a tile 8 KiB (two 1-KiB copy instructions per wave) and a
+// half tile four MFMAs instead of eight, each followed by two softmax slices instead of one.
 #include <cstdint>
 
 #include "common.hip.h"
 #include "kernels.h"
 
+#if !defined(PK_D) || !defined(PK_DNS) || (PK_D != 128 && PK_D != 64)
+#error "define PK_D (128 or 64) and PK_DNS before including prefill_body.hip.h"
+#endif
+
 namespace pk {
 namespace {
+namespace PK_DNS {
 
-constexpr int BM = 128, BN = 64, D = 128;
+constexpr int BM = 128, BN = 64, D = PK_D;
 constexpr int ROWB = D * 2;                        // bytes per K/V row in LDS (unpadded)
-constexpr int TILE_BYTES = BN * ROWB;              // 16 KiB
+constexpr int TILE_BYTES = BN * ROWB;              // 16 KiB (8 KiB for D = 64)
 constexpr int KS = D / 16, DB = D / 32;
+constexpr int PIECES = TILE_BYTES / 4096;          // 1-KiB copy instructions per wave and tile
+constexpr int WAVE_PART = TILE_BYTES / 4;          // bytes of a stage that one wave fills
 
 typedef bf16x4 __attribute__((address_space(3))) * lds_bf16x4_ptr;
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
 
 // chunk position p of row `row` holds logical chunk p ^ swz(row)
+#if PK_D == 128
 __device__ __forceinline__ int swz(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
+#else
+// 128-byte rows: two rows share a line of the 64 banks, so rows of the same parity need eight
+// different values (K row reads of 16 consecutive rows), and rows r and r + 2 must differ in
+// bit 2 (the transpose reads take 64 bytes from each of four consecutive rows)
+__device__ __forceinline__ int swz(int row) { const int x = (row >> 1) & 7; return ((x & 1) << 2) | (x >> 1); }
+#endif
 
 struct LaneOffsets {
     int k[KS];          // K operand read: row n, logical chunk 2 st + hlf (add 32 kb rows)
     int v1[DB];         // V transpose read of column block b, rows +0..3 (add (32 kb + 16 t) rows); the read
                         // of rows +8..11 is at (v1 ^ 32) + 8 rows: its swizzle differs in one bit
-    int g[4];           // global byte offsets of this lane's four copy instructions
+#if PK_D == 64
+    int v2[DB];         // (128-byte rows: the read of rows +8..11 has an offset of its own)
+#endif
+    int g[PIECES];      // global byte offsets of this lane's copy instructions
 };
 
 __device__ __forceinline__ bf16x8 v_operand(const unsigned char* vs, const LaneOffsets& lo, int kb, int t, int b) {
     const unsigned char* p = vs + (32 * kb + 16 * t) * ROWB;
     const bf16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)(p + lo.v1[b]));
+#if PK_D == 128
     const bf16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)(p + 8 * ROWB + (lo.v1[b] ^ 32)));
+#else
+    const bf16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)(p + lo.v2[b]));
+#endif
     return __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
 }
 
@@ -90,19 +113,34 @@ __device__ __forceinline__ bool setup(const PrefillArgs& a, const int block, Wor
 #pragma unroll
     for (int st = 0; st < KS; ++st) off.k[st] = u.n * ROWB + (((2 * st + u.hlf) ^ fl) << 4);
     const int i16 = u.lane & 15, gl = (u.lane >> 4) & 1, r4 = i16 >> 2;
-    const int f1 = (r4 << 2) | u.hlf;  // rows +8: (hlf + 2) & 3 = hlf ^ 2, i.e. chunk ^ 2, byte offset ^ 32
     const int rowl = 4 * u.hlf + r4, byte = (i16 & 1) * 8;
+#if PK_D == 128
+    const int f1 = (r4 << 2) | u.hlf;  // rows +8: (hlf + 2) & 3 = hlf ^ 2, i.e. chunk ^ 2, byte offset ^ 32
 #pragma unroll
     for (int b = 0; b < DB; ++b) {
         const int c = 4 * b + 2 * gl + ((i16 & 3) >> 1);
         off.v1[b] = rowl * ROWB + ((c ^ f1) << 4) + byte;
     }
-    const int r_in = u.lane >> 4, pos = u.lane & 15;
+    const int r_in = u.lane >> 4, pos = u.lane & 15;   // a copy instruction takes 4 rows of 16 chunks
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         const int row = 16 * u.wave + 4 * q + r_in;
         off.g[q] = static_cast<int>(row * u.row_bytes + u.kvh * ROWB + ((pos ^ swz(row)) << 4));
     }
+#else
+#pragma unroll
+    for (int b = 0; b < DB; ++b) {
+        const int c = 4 * b + 2 * gl + ((i16 & 3) >> 1);
+        off.v1[b] = rowl * ROWB + ((c ^ swz(rowl)) << 4) + byte;
+        off.v2[b] = (rowl + 8) * ROWB + ((c ^ swz(rowl + 8)) << 4) + byte;
+    }
+    const int r_in = u.lane >> 3, pos = u.lane & 7;    // a copy instruction takes 8 rows of 8 chunks
+#pragma unroll
+    for (int q = 0; q < PIECES; ++q) {
+        const int row = 16 * u.wave + 8 * q + r_in;
+        off.g[q] = static_cast<int>(row * u.row_bytes + u.kvh * ROWB + ((pos ^ swz(row)) << 4));
+    }
+#endif
     // Q operand: lane (n, hlf) holds Q[row n][16s + 8hlf .. +8].  Only requested here: the caller
     // scales it (scale_q) after it has requested the first K/V tiles, so that the two round trips
     // to memory overlap.
@@ -161,15 +199,17 @@ __device__ __forceinline__ void store_output(const PrefillArgs& a, const WorkUni
 }
 
 // bf16 output through LDS, so that every row leaves as whole 16-byte pieces (four rows of 256
-// bytes per store instruction) instead of 8-byte pieces of 32 different rows.  The wave uses two
-// 4-KiB pieces of LDS that belong to it alone (rows 0..15 in qa, rows 16..31 in qb); the 16-byte
-// chunks of a row are XOR-swizzled with the row number, which keeps both sides off bank conflicts.
+// bytes, or eight of 128, per store instruction) instead of 8-byte pieces of 32 different rows.
+// The wave uses two pieces of LDS of 16 rows each that belong to it alone (rows 0..15 in qa, rows
+// 16..31 in qb); the 16-byte chunks of a row are XOR-swizzled with the row number, which keeps
+// both sides off bank conflicts.
 __device__ __forceinline__ void store_output_bf16(const PrefillArgs& a, const WorkUnit& u, const floatx16 (&o)[DB],
                                                   float l, unsigned char* qa, unsigned char* qb) {
     {
         const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(l), __float_as_uint(l), false, false);
         l = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
     }
+    constexpr int CPR = D / 8, RPI = 64 / CPR;     // 16-byte chunks per row; rows per store instruction
     const float inv = l > 0.f ? 1.f / l : 0.f;
     const int rr = u.n & 15;
     unsigned char* wrow = (u.n < 16 ? qa : qb) + rr * ROWB + 8 * u.hlf;
@@ -179,14 +219,14 @@ __device__ __forceinline__ void store_output_bf16(const PrefillArgs& a, const Wo
         for (int q4 = 0; q4 < 4; ++q4) {       // columns 32b + 8q4 + 4hlf .. +3: chunk 4b + q4, half hlf
             const float x0 = o[b][4 * q4] * inv, x1 = o[b][4 * q4 + 1] * inv;
             const float x2 = o[b][4 * q4 + 2] * inv, x3 = o[b][4 * q4 + 3] * inv;
-            *reinterpret_cast<uint2*>(wrow + (((4 * b + q4) ^ rr) << 4)) =
+            *reinterpret_cast<uint2*>(wrow + (((4 * b + q4) ^ (rr & (CPR - 1))) << 4)) =
                 make_uint2(pack_bf16x2(x0, x1), pack_bf16x2(x2, x3));
         }
-    const int chunk = u.lane & 15;
+    const int chunk = u.lane & (CPR - 1);
 #pragma unroll
-    for (int k = 0; k < 8; ++k) {
-        const int row = 4 * k + (u.lane >> 4), r2 = row & 15;
-        const u32x4 v = *reinterpret_cast<const u32x4*>((row < 16 ? qa : qb) + r2 * ROWB + ((chunk ^ r2) << 4));
+    for (int k = 0; k < 32 / RPI; ++k) {
+        const int row = RPI * k + u.lane / CPR, r2 = row & 15;
+        const u32x4 v = *reinterpret_cast<const u32x4*>((row < 16 ? qa : qb) + r2 * ROWB + ((chunk ^ (r2 & (CPR - 1))) << 4));
         const int qrow = __shfl(u.qrow, row, 64);
         if (qrow >= 0)
             *reinterpret_cast<u32x4*>(static_cast<uint16_t*>(a.out) +
@@ -194,7 +234,8 @@ __device__ __forceinline__ void store_output_bf16(const PrefillArgs& a, const Wo
     }
 }
 
-// Copies of K/V tiles into LDS stages.  A tile is 16 instructions of 1 KiB (four per wave), each
+// Copies of K/V tiles into LDS stages.  A tile is 16 instructions of 1 KiB (four per wave; eight and
+// two for D = 64), each
 // lane fetching the 16-byte chunk that belongs at its (swizzled) LDS position; rows past the end
 // of the array arrive as zeros (the descriptor's size is what is left of the array; a tile past
 // the end of the key-tile list gets size 0: zeros, no memory traffic).  The copy is issued from
@@ -226,7 +267,7 @@ __device__ __forceinline__ void lds_copy_16(const u32x4& rsrc, uint32_t lds_addr
 #define PK_COPY_TILE(SRC, KSTART, DST, ENABLED)                                              \
     {                                                                                        \
         PK_TILE_DESC(rs_, SRC, KSTART, ENABLED)                                              \
-        _Pragma("unroll") for (int q = 0; q < 4; ++q) PK_COPY_PIECE(rs_, DST, q);            \
+        _Pragma("unroll") for (int q = 0; q < PIECES; ++q) PK_COPY_PIECE(rs_, DST, q);       \
     }
 #define PK_WAIT_ALL_COPIES() __builtin_amdgcn_s_waitcnt(0x0F70)      /* vmcnt(0) */
 #define PK_CODE(INFO) (((INFO) >> (8 + 2 * u.wave)) & 3)          /* 0 skip, 1 masked, 2 unmasked */
@@ -369,17 +410,17 @@ __device__ __forceinline__ bf16x8 k_operand(const unsigned char* ks, const LaneO
     return *reinterpret_cast<const bf16x8*>(ks + lo.k[x] + half * 32 * ROWB);
 }
 __device__ __forceinline__ bf16x8 v_operand_x(const unsigned char* vs, const LaneOffsets& lo, int half, int x) {
-    return v_operand(vs, lo, half, x >> 2, x & 3);
+    return v_operand(vs, lo, half, x / DB, x % DB);
 }
-// Operand stream of a tile: 0..7 K(half 0), 8..15 K(half 1), 16..23 V(half 0), 24..31 V(half 1),
-// 32..35 the first K operands of the next tile.  MFMA k takes ring[k % 4] and then refills that
+// Operand stream of a tile (KS operands per half tile; shown for D = 128): 0..7 K(half 0), 8..15
+// K(half 1), 16..23 V(half 0), 24..31 V(half 1), 32..35 the first K operands of the next tile.  MFMA k takes ring[k % 4] and then refills that
 // slot with operand k + 4, so that every LDS read has four MFMAs (and their vector slices) to land.
 template <int K>
 __device__ __forceinline__ bf16x8 stream_operand(const unsigned char* k_cur, const unsigned char* v_cur,
                                                  const unsigned char* k_next, const LaneOffsets& off) {
-    if constexpr (K < 16) return k_operand(k_cur, off, K >> 3, K & 7);
-    else if constexpr (K < 32) return v_operand_x(v_cur, off, (K - 16) >> 3, K & 7);
-    else return k_operand(k_next, off, 0, K - 32);
+    if constexpr (K < 2 * KS) return k_operand(k_cur, off, K / KS, K % KS);
+    else if constexpr (K < 4 * KS) return v_operand_x(v_cur, off, (K - 2 * KS) / KS, K % KS);
+    else return k_operand(k_next, off, 0, K - 4 * KS);
 }
 #define PK_REFILL(K0) ring[i & 3] = stream_operand<(K0) + i + 4>(lds + k_cur, lds + v_cur, lds + k_next, off)
 #define PK_SLICE(C, S, H, ACC, BODY)                                                          \
@@ -390,6 +431,7 @@ __device__ __forceinline__ bf16x8 stream_operand(const unsigned char* k_cur, con
         softmax_slice<C>(S, H);                                                                \
         pin_slice_outputs<C>(ring[(C + 1) & 3], H);                                            \
     }
+#if PK_D == 128
 // eight MFMAs (BODY, with accumulator ACC) interleaved with the softmax of the scores S
 #define PK_SLICES(S, H, ACC, BODY)                                                             \
     PK_SLICE(0, S, H, ACC, BODY) PK_SLICE(1, S, H, ACC, BODY) PK_SLICE(2, S, H, ACC, BODY)       \
@@ -407,6 +449,30 @@ __device__ __forceinline__ bf16x8 stream_operand(const unsigned char* k_cur, con
         { constexpr int i = 6; BODY; __builtin_amdgcn_sched_barrier(0); }                      \
         { constexpr int i = 7; BODY; __builtin_amdgcn_sched_barrier(0); }                      \
     }
+#else
+// D = 64: four MFMAs per half tile, each followed by two of the eight softmax slices
+#define PK_SLICE2(I, S, H, ACC, BODY)                                                          \
+    {                                                                                          \
+        constexpr int i = I;                                                                   \
+        BODY;                                                                                  \
+        pin_slice_inputs<I>(ACC, S);                                                           \
+        softmax_slice<2 * (I)>(S, H);                                                          \
+        softmax_slice<2 * (I) + 1>(S, H);                                                      \
+        pin_slice_outputs<2 * (I)>(ring[((I) + 1) & 3], H);                                    \
+        pin_slice_outputs<2 * (I) + 1>(ring[((I) + 1) & 3], H);                                \
+    }
+#define PK_SLICES(S, H, ACC, BODY)                                                             \
+    PK_SLICE2(0, S, H, ACC, BODY) PK_SLICE2(1, S, H, ACC, BODY) PK_SLICE2(2, S, H, ACC, BODY)    \
+    PK_SLICE2(3, S, H, ACC, BODY)
+
+#define PK_EIGHT(BODY)                                                                         \
+    {                                                                                          \
+        { constexpr int i = 0; BODY; __builtin_amdgcn_sched_barrier(0); }                      \
+        { constexpr int i = 1; BODY; __builtin_amdgcn_sched_barrier(0); }                      \
+        { constexpr int i = 2; BODY; __builtin_amdgcn_sched_barrier(0); }                      \
+        { constexpr int i = 3; BODY; __builtin_amdgcn_sched_barrier(0); }                      \
+    }
+#endif
 
 // `block`: the workgroup's number in the prefill launch order; `lds`: 5 * TILE_BYTES, 1 KiB aligned
 // (K stages 0..2, V stages 3..4).
@@ -435,7 +501,7 @@ __device__ __forceinline__ void prefill_tile_body(const PrefillArgs& a, const in
     floatx16 negm = {};
 
     // this wave's quarter of a stage, as a scalar
-    const uint32_t lds_wave = __builtin_amdgcn_readfirstlane(lds_base + u.wave * 4096);
+    const uint32_t lds_wave = __builtin_amdgcn_readfirstlane(lds_base + u.wave * WAVE_PART);
     // window of tile-list entries: e0 = tile j, e1 = tile j+1, e2 = tile j+2 (e3 is fetched for the next turn)
     int e0s, e0i, e1s, e1i, e2s, e2i;
     entry(0, e0s, e0i); entry(1, e1s, e1i); entry(2, e2s, e2i);
@@ -462,8 +528,8 @@ __device__ __forceinline__ void prefill_tile_body(const PrefillArgs& a, const in
     PK_TILE_DESC(rs_k, a.k, e2s, j + 2 < n_kv)                                                 \
     PK_TILE_DESC(rs_v, a.v, e1s, j + 1 < n_kv)
 #define PK_COPY_STEP(I)                                                                       \
-    if constexpr ((I) < 4) PK_COPY_PIECE(rs_k, k_fill, (I));                                   \
-    else PK_COPY_PIECE(rs_v, v_fill, (I) - 4);
+    if constexpr ((I) < PIECES) PK_COPY_PIECE(rs_k, k_fill, (I));                              \
+    else PK_COPY_PIECE(rs_v, v_fill, (I) - PIECES);
     // (the next list entry is fetched right before the barrier: scalar loads and LDS reads share a
     // counter and return out of order, so the first wait after the fetch drains the operand ring;
     // here the ring has the whole barrier to land anyway)
@@ -481,7 +547,7 @@ __device__ __forceinline__ void prefill_tile_body(const PrefillArgs& a, const in
     for (; j < u.n_lead; ++j) {
         PK_TILE_BEGIN();
 #pragma unroll
-        for (int q = 0; q < 4; ++q) { PK_COPY_PIECE(rs_k, k_fill, q); PK_COPY_PIECE(rs_v, v_fill, q); }
+        for (int q = 0; q < PIECES; ++q) { PK_COPY_PIECE(rs_k, k_fill, q); PK_COPY_PIECE(rs_v, v_fill, q); }
         PK_TILE_END();
     }
     if (u.n_lead > 0) {
@@ -501,7 +567,7 @@ __device__ __forceinline__ void prefill_tile_body(const PrefillArgs& a, const in
         h0.l0 = 0.f; h0.l1 = 0.f; h1.l0 = 0.f; h1.l1 = 0.f;
         if (masked) mask_half(s0, 0, u.lo, hi_t, k_start, u.hlf);    // unmasked tiles skip the compares
         PK_SLICES(s0, h0, s1, s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[i & 3], qf[i], i == 0 ? negm : s1, 0, 0, 0);
-                  PK_REFILL(8));
+                  PK_REFILL(KS));
         PK_SOFTMAX_CHECK(s0, h0, if (slow) {                      /* S1 was started at the old reference */
             _Pragma("unroll") for (int e = 0; e < 16; ++e) s1[e] -= delta;
         })
@@ -510,22 +576,22 @@ __device__ __forceinline__ void prefill_tile_body(const PrefillArgs& a, const in
         for (int t = 0; t < 2; ++t)
             p0[t] = __builtin_bit_cast(bf16x8, u32x4{h0.pw[4 * t], h0.pw[4 * t + 1], h0.pw[4 * t + 2], h0.pw[4 * t + 3]});
         if (masked) mask_half(s1, 1, u.lo, hi_t, k_start, u.hlf);
-        PK_SLICES(s1, h1, o[i & 3], o[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[i & 3], p0[i >> 2], o[i & 3], 0, 0, 0);
-                  PK_REFILL(16));
+        PK_SLICES(s1, h1, o[i % DB], o[i % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[i & 3], p0[i / DB], o[i % DB], 0, 0, 0);
+                  PK_REFILL(2 * KS));
         PK_SOFTMAX_CHECK(s1, h1, )
 #pragma unroll
         for (int t = 0; t < 2; ++t)
             p1[t] = __builtin_bit_cast(bf16x8, u32x4{h1.pw[4 * t], h1.pw[4 * t + 1], h1.pw[4 * t + 2], h1.pw[4 * t + 3]});
         // phase 4; its last refills are the first operands of the next tile
-        PK_EIGHT(o[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[i & 3], p1[i >> 2], o[i & 3], 0, 0, 0);
-                 PK_REFILL(24));
+        PK_EIGHT(o[i % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[i & 3], p1[i / DB], o[i % DB], 0, 0, 0);
+                 PK_REFILL(3 * KS));
         PK_TILE_END();
     }
     // trailing tiles that this wave skips: it only takes part in the copies and in the barriers
     for (; j < n_kv; ++j) {
         PK_TILE_BEGIN();
 #pragma unroll
-        for (int q = 0; q < 4; ++q) { PK_COPY_PIECE(rs_k, k_fill, q); PK_COPY_PIECE(rs_v, v_fill, q); }
+        for (int q = 0; q < PIECES; ++q) { PK_COPY_PIECE(rs_k, k_fill, q); PK_COPY_PIECE(rs_v, v_fill, q); }
         PK_TILE_END();
     }
     // After the last barrier nobody reads or fills the two stages that would have taken tiles
@@ -533,7 +599,7 @@ __device__ __forceinline__ void prefill_tile_body(const PrefillArgs& a, const in
     // ever touch its own quarter of a stage: those two quarters stage this wave's output.
     PK_WAIT_ALL_COPIES();                          // (none is outstanding here; kept as a guard)
     if (a.out_f32) store_output(a, u, o, l);
-    else store_output_bf16(a, u, o, l, lds + k_next + u.wave * 4096, lds + v_cur + u.wave * 4096);
+    else store_output_bf16(a, u, o, l, lds + k_next + u.wave * WAVE_PART, lds + v_cur + u.wave * WAVE_PART);
 }
 
 #undef PK_COPY_TILE
@@ -544,11 +610,13 @@ __device__ __forceinline__ void prefill_tile_body(const PrefillArgs& a, const in
 #undef PK_TILE_BEGIN
 #undef PK_TILE_END
 #undef PK_SLICE
+#undef PK_SLICE2
 #undef PK_SLICES
 #undef PK_EIGHT
 #undef PK_REFILL
 #undef PK_WAIT_ALL_COPIES
 #undef PK_CODE
 
+}  // namespace PK_DNS
 }  // namespace
 }  // namespace pk

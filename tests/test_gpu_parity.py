@@ -21,8 +21,10 @@ def to_dev(w):
     return w
 
 
-def run_prefill(w, use_f32, padded=False, out_f32=True, budget=None):
+def run_prefill(w, use_f32, padded=False, out_f32=True, budget=None, pipeline=0):
     plan = pk.pack_plan(w.kv_lens, w.q_lens, token_budget=budget or w.token_budget)
+    if pipeline:
+        plan.tune(pk.TUNE_PREFILL_PIPELINE, pipeline)
     q, k, v = (w.q_f32, w.k_f32, w.v_f32) if use_f32 else (w.q, w.k, w.v)
     code = pk.PK_F32 if use_f32 else pk.PK_BF16
     ws = pk.new_workspace(plan, w.Hq, w.Hkv, w.d, code)
@@ -151,6 +153,20 @@ def test_prefill_small(use_f32, case):
     H.assert_close(got_p, want, 1 if use_f32 else 0, f"padded prefill {case}")
 
 
+@pytest.mark.parametrize("pipeline", [0, 1])
+def test_prefill_d64_long_key_lists(pipeline):
+    """Head dimension 64 over many key tiles: requests of several thousand tokens (one with prior
+    context, one that ends inside a tile shared with the next), grouped query heads, both pipelines."""
+    kv = np.asarray([3000, 1100 + 700, 257, 64, 5], dtype=np.int32)
+    ql = np.asarray([3000, 1100, 257, 64, 5], dtype=np.int32)
+    w = to_dev(wl.make_ragged("d64_long", kv, ql, 8, 2, 64, 2048, 17, keep_f32=False))
+    want = H.oracle_ragged(w, False)
+    for padded in (False, True):
+        got, plan = run_prefill(w, False, padded=padded, out_f32=not padded, pipeline=pipeline)
+        H.assert_close(got, want, 0, f"d = 64, long lists, padded={padded}, pipeline={pipeline}")
+        assert plan.stat(7 if padded else 6) > 30
+
+
 @pytest.mark.parametrize("seed", [0, 1])
 def test_config1_tiny_prefill_full(seed):
     w = to_dev(wl.config1(seed))
@@ -213,6 +229,9 @@ def test_config2_prefill_full_size_every_row(seed):
     H.assert_close(got, want, 0, f"cfg2 seed {seed} packed, all rows")
     got_pad, _ = run_prefill(w, False, padded=True, out_f32=False)
     H.assert_close(got_pad, want, 0, f"cfg2 seed {seed} padded, all rows")
+    if seed == 0:                  # the register-staged pipeline (pk_plan_tune), same schedule and arithmetic
+        got_st, _ = run_prefill(w, False, out_f32=False, pipeline=1)
+        H.assert_close(got_st, want, 0, "cfg2 seed 0 packed, staged pipeline, all rows")
     # first causal row of every request returns v[0] of its KV head (up to bf16 rounding of the output)
     v = w.v.float().cpu().numpy()
     qs, ks = w.q_start, w.kv_start

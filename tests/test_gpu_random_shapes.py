@@ -37,15 +37,17 @@ def test_prefill_random_shapes(seed):
     budget = int(rng.choice([64, 200, 512, 1024, 4096]))
     w = to_dev(wl.make_ragged(f"rand{seed}", ql + ctx, ql, Hq, Hkv, d, budget, seed, keep_f32=False))
     want = H.oracle_ragged(w, False)
-    for padded in (False, True):
+    for padded, pipeline in ((False, 0), (True, 0), (False, 1), (True, 1)):     # pipeline 1: staged through registers
         plan = pk.pack_plan(w.kv_lens, w.q_lens, token_budget=budget)
+        plan.tune(pk.TUNE_PREFILL_PIPELINE, pipeline)
         ws = pk.new_workspace(plan, w.Hq, w.Hkv, w.d, pk.PK_BF16)
         out = torch.full(w.q.shape, float("nan"), dtype=torch.bfloat16 if seed % 2 else torch.float32, device=DEV)
         fn = pk.padded_prefill_attn if padded else pk.packed_prefill_attn
         fn(plan, w.q, w.k, w.v, out, w.scale, ws)
         torch.cuda.synchronize()
         H.assert_close(out.float().cpu().numpy(), want, 0,
-                       f"seed {seed} padded={padded} n={n} Hq={Hq} Hkv={Hkv} d={d} C={budget} q={ql.tolist()} ctx={ctx.tolist()}")
+                       f"seed {seed} padded={padded} pipeline={pipeline} n={n} Hq={Hq} Hkv={Hkv} d={d} C={budget} "
+                       f"q={ql.tolist()} ctx={ctx.tolist()}")
 
 
 @pytest.mark.parametrize("seed", range(8))

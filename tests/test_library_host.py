@@ -359,4 +359,9 @@ def test_tune_decode_split_changes_only_the_schedule():
     assert np.array_equal(plan.words(), words)
     L = pk.lib()
     assert L.pk_plan_tune(plan.handle, 99, 1) == -1 and L.pk_plan_tune(plan.handle, 0, -5) == -1
+    # the prefill pipeline knob takes 0 or 1 and leaves plan and tables alone
+    assert L.pk_plan_tune(plan.handle, pk.TUNE_PREFILL_PIPELINE, 2) == -1
+    plan.tune(pk.TUNE_PREFILL_PIPELINE, 1)
+    plan.tune(pk.TUNE_PREFILL_PIPELINE, 0)
+    assert plan.stat(5) == auto_split and np.array_equal(plan.words(), words)
     assert L.pk_plan_tune(None, 0, 0) == -1
