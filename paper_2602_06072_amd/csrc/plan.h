@@ -17,6 +17,7 @@ constexpr int kPrefillBM = 128;     // query rows per workgroup tile (4 waves x 
 constexpr int kPrefillBN = 64;      // keys per K/V tile
 constexpr int kDecodeBlock = PK_KV_BLOCK;   // tokens per buffer tile
 constexpr int kDecodeMaxRows = 32;  // query rows (members x heads-per-KV-head) per work item
+constexpr int kTileDescWords = 16;  // int32 words per query-tile descriptor of the prefill schedules (one 64-byte scalar load)
 
 struct Member {                     // O_g[i] of Alg. 1 Part 2, offsets relative to the group base
     int32_t req, prefix_off, lp, suffix_off, lq;   // prefix_off / lp: the innermost shared segment (suffix_off / 0: none)

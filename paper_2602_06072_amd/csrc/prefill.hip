@@ -60,7 +60,7 @@ __global__ __launch_bounds__(256, 2) void prefill_bf16_kernel(PrefillArgs a) {
     } else {
         tile = blockIdx.x / a.Hq; head = blockIdx.x % a.Hq; kvh = head / r;
     }
-    const int32_t* desc = a.tiles + 8 * static_cast<int64_t>(tile);
+    const int32_t* desc = a.tiles + 16 * static_cast<int64_t>(tile);     // (16 words per descriptor; this kernel uses the first 8)
     const int kv_first = desc[0], n_kv = desc[1];
     if (n_kv == 0) return;
 

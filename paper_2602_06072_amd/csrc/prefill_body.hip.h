@@ -74,6 +74,7 @@ __device__ __forceinline__ bf16x8 v_operand(const unsigned char* vs, const LaneO
 // What a workgroup works on, and this lane's share of it.
 struct WorkUnit {
     int head, kvh, n_kv, n_lead, n_active, wave, lane, n, hlf;   // this wave computes key tiles [n_lead, n_active)
+    int ks0, ks1;                      // first key rows of the tile's first two key tiles
     int qrow, lo, hi;                  // this lane's query row (-1: padding) and its key range [lo, hi)
     const int32_t* kvt;                // key-tile list of the query tile: (first key row, info) pairs
     int64_t row_bytes;                 // bytes between consecutive K/V rows in global memory
@@ -93,12 +94,14 @@ __device__ __forceinline__ bool setup(const PrefillArgs& a, const int block, Wor
     } else {
         tile = block / a.Hq; u.head = block % a.Hq; u.kvh = u.head / r;
     }
-    // everything about the tile in one 32-byte scalar load
-    typedef int32_t i32x8 __attribute__((ext_vector_type(8)));
-    const i32x8 desc = *(const __attribute__((address_space(4))) i32x8*)(a.tiles + 8 * static_cast<int64_t>(tile));
+    // everything about the tile in one 64-byte scalar load, including the first key rows of its first
+    // key tiles: the first K/V copies do not wait for the key-tile list
+    typedef int32_t i32x16 __attribute__((ext_vector_type(16)));
+    const i32x16 desc = *(const __attribute__((address_space(4))) i32x16*)(a.tiles + 16 * static_cast<int64_t>(tile));
     u.n_kv = desc[1];
     if (u.n_kv == 0) return false;
     u.kvt = a.kvtiles + 2 * static_cast<int64_t>(desc[0]);
+    u.ks0 = desc[8]; u.ks1 = desc[9];
     const int tid = threadIdx.x;
     u.lane = tid & 63; u.n = u.lane & 31; u.hlf = u.lane >> 5;
     u.wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -505,10 +508,10 @@ __device__ __forceinline__ void prefill_tile_body(const PrefillArgs& a, const in
     // window of tile-list entries: e0 = tile j, e1 = tile j+1, e2 = tile j+2 (e3 is fetched for the next turn)
     int e0s, e0i, e1s, e1i, e2s, e2i;
     entry(0, e0s, e0i); entry(1, e1s, e1i); entry(2, e2s, e2i);
-    // prologue: K(0), K(1), V(0)
-    PK_COPY_TILE(a.k, e0s, 0, true);
-    PK_COPY_TILE(a.k, e1s, TILE_BYTES, 1 < n_kv);
-    PK_COPY_TILE(a.v, e0s, 3 * TILE_BYTES, true);
+    // prologue: K(0), K(1), V(0), from the key rows in the descriptor (the entries above arrive meanwhile)
+    PK_COPY_TILE(a.k, u.ks0, 0, true);
+    PK_COPY_TILE(a.k, u.ks1, TILE_BYTES, 1 < n_kv);
+    PK_COPY_TILE(a.v, u.ks0, 3 * TILE_BYTES, true);
     scale_q(qf, a.scale * kLog2e);                 // (waits for the Q loads, which were requested first)
     PK_WAIT_ALL_COPIES();
     __syncthreads();

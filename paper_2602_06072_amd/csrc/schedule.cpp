@@ -284,7 +284,7 @@ void add_idle_tile(SchedBuild& sb) {               // padded grid slot of a requ
 void emit_sched(const SchedBuild& sb, const std::vector<int32_t>& order, Builder& b,
                 DeviceTables::PrefillSched& s) {
     std::vector<int32_t> desc, more_first, more, kv;
-    desc.reserve(order.size() * 8);
+    desc.reserve(order.size() * kTileDescWords);
     more_first.reserve(order.size());
     kv.reserve(sb.kv.size());
     for (int32_t idx : order) {
@@ -313,6 +313,14 @@ void emit_sched(const SchedBuild& sb, const std::vector<int32_t>& order, Builder
         const int32_t* run = sb.runs.data() + 4 * static_cast<size_t>(sb.run_first[idx]);
         desc.push_back(sb.n_rows[idx] | (nr << 16));
         for (int x = 1; x < 4; ++x) desc.push_back(nr > 0 ? run[x] : 0);
+        // words 8..10: the first key rows of the tile's first three key tiles (the last one repeated
+        // if there are fewer), so that the kernel can request its first K/V tiles without waiting for
+        // a look-up in the key-tile list; the rest pads the descriptor to 64 bytes
+        for (int e = 0; e < 3; ++e) {
+            const int32_t ee = sb.n_kv[idx] > 0 ? std::min(e, sb.n_kv[idx] - 1) : 0;
+            desc.push_back(sb.n_kv[idx] > 0 ? sb.kv[2 * (static_cast<size_t>(sb.kv_first[idx]) + ee)] : 0);
+        }
+        for (int x = 11; x < kTileDescWords; ++x) desc.push_back(0);
         more_first.push_back(static_cast<int32_t>(more.size() / 4));
         if (nr > 1) more.insert(more.end(), run + 4, run + 4 * static_cast<size_t>(nr));
         kv.insert(kv.end(), sb.kv.begin() + 2 * sb.kv_first[idx], sb.kv.begin() + 2 * (sb.kv_first[idx] + sb.n_kv[idx]));
@@ -435,7 +443,7 @@ size_t padded_bound_bytes(const pk_plan& plan) {
             kv_entries += (ctx + std::min<int64_t>(plan.q_lens[i], (tt + 1) * BM) + BN - 1) / BN;
     }
     const int64_t tiles = max_tiles * plan.n;
-    const int64_t ints = tiles * 8 + tiles + 2 * kv_entries + 6 * 64;   // a padded tile is one run: the run list is empty
+    const int64_t ints = tiles * kTileDescWords + tiles + 2 * kv_entries + 6 * 64;   // a padded tile is one run: the run list is empty
     return static_cast<size_t>((ints + 63) / 64 * 64) * sizeof(int32_t);
 }
 
