@@ -25,7 +25,7 @@ def to_dev(w):
 EDGE = np.array([1, 2, 31, 32, 33, 63, 64, 65, 96, 127, 128, 129, 160, 191, 192, 255, 256, 257, 300, 383, 384, 513])
 
 
-@pytest.mark.parametrize("seed", range(12))
+@pytest.mark.parametrize("seed", range(32))
 def test_prefill_random_shapes(seed):
     rng = np.random.default_rng(1000 + seed)
     n = int(rng.integers(1, 18))
@@ -50,7 +50,7 @@ def test_prefill_random_shapes(seed):
                        f"q={ql.tolist()} ctx={ctx.tolist()}")
 
 
-@pytest.mark.parametrize("seed", range(8))
+@pytest.mark.parametrize("seed", range(24))
 def test_decode_random_shapes(seed):
     rng = np.random.default_rng(2000 + seed)
     n = int(rng.integers(1, 40))
