@@ -418,6 +418,7 @@ int64_t pk_plan_stat(const pk_plan* plan, int what);
  *                            (default); 1 = staged through registers, two
  *                            stages with padded rows.  Same tile shape (128
  *                            query rows x 64 keys), same arithmetic.
+ *                            (pk_packed_mixed_step always runs pipeline 0.)
  * Errors: PK_EINVAL (NULL plan, unknown knob, value out of range). */
 #define PK_TUNE_DECODE_SPLIT 0
 #define PK_TUNE_PREFILL_PIPELINE 1
