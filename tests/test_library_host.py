@@ -365,3 +365,40 @@ def test_tune_decode_split_changes_only_the_schedule():
     plan.tune(pk.TUNE_PREFILL_PIPELINE, 0)
     assert plan.stat(5) == auto_split and np.array_equal(plan.words(), words)
     assert L.pk_plan_tune(None, 0, 0) == -1
+
+
+def test_plans_made_concurrently_on_several_host_threads_equal_the_oracle():
+    """The header allows different plans on different host threads: eight threads make, size and
+    query plans of their own at the same time (ctypes releases the interpreter lock inside the
+    calls); every plan equals the oracle's, and an error on one thread leaves the others' last-error
+    text alone."""
+    import threading
+    rng = np.random.default_rng(77)
+    jobs = []
+    for _ in range(64):
+        n = int(rng.integers(1, 60))
+        kv = rng.integers(1, 3000, size=n).astype(np.int32)
+        C = int(rng.choice([256, 1024, 4096, 16384]))
+        jobs.append((kv, C, oracle_words(kv, None, None, None, C, 0)))
+    failures = []
+
+    def worker(tid):
+        try:
+            for j in range(tid, len(jobs), 8):
+                kv, C, want = jobs[j]
+                plan = pk.pack_plan(kv, None, None, None, C, 0)
+                assert np.array_equal(plan.words(), want)
+                assert plan.workspace_bytes(8, 2, 128, pk.PK_BF16) > 0 and plan.stat(6) > 0
+                if tid == 0:
+                    assert pk.lib().pk_plan_tune(plan.handle, 99, 1) == -1
+                    assert b"unknown knob" in pk.lib().pk_last_error()
+                else:
+                    assert b"unknown knob" not in pk.lib().pk_last_error()
+        except Exception as e:       # noqa: BLE001 (reported below, on the main thread)
+            failures.append((tid, repr(e)))
+    threads = [threading.Thread(target=worker, args=(t,)) for t in range(8)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not failures, failures
