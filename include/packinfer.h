@@ -213,6 +213,7 @@ int pk_kv_reorganize(pk_plan* plan, const void* k_pages, const void* v_pages,
  *
  *   q    device [sum q_lens][Hq][d]    k, v  device [sum kv_lens][Hkv][d]
  *   out  device [sum q_lens][Hq][d], out_dtype
+ *   scale  finite and positive (here and in every attention call below)
  * Errors: PK_EINVAL; PK_EUNSUPPORTED (bf16 path: d in {64,128}, Hq % Hkv == 0).
  */
 int pk_packed_prefill_attn(pk_plan* plan, const void* q, const void* k, const void* v,

@@ -1,6 +1,7 @@
 // C ABI: argument validation, binding of plan tables to a workspace, launches.
 #include <hip/hip_runtime_api.h>
 
+#include <cmath>
 #include <cstring>
 #include <initializer_list>
 #include <mutex>
@@ -254,6 +255,7 @@ static int prefill_common(pk_plan* plan, const void* q, const void* k, const voi
     if (!aligned16({q, k, v, out})) return fail(PK_EINVAL, std::string(who) + ": tensors must be 16-byte aligned");
     if (!shape_ok(Hq, Hkv, d, dtype, why)) return fail(PK_EINVAL, std::string(who) + ": " + why);
     if (out_dtype != PK_BF16 && out_dtype != PK_F32) return fail(PK_EINVAL, std::string(who) + ": bad out_dtype");
+    if (!(scale > 0.f) || !std::isfinite(scale)) return fail(PK_EINVAL, std::string(who) + ": scale must be finite and positive");
     if (dtype == PK_BF16 && d != 64 && d != 128) return fail(PK_EUNSUPPORTED, std::string(who) + ": bf16 path needs d in {64,128}");
     if (dtype == PK_F32 && d > 256) return fail(PK_EUNSUPPORTED, std::string(who) + ": fp32 path needs d <= 256");
     int rc = ensure_bound(plan, Hq, Hkv, d, dtype, workspace, workspace_bytes, stream);
@@ -319,6 +321,7 @@ int decode_common(const char* who, pk_plan* plan, const void* q, const void* kv_
         return fail(PK_EINVAL, w + ": grown must be in [0, headroom] (regroup when the headroom is used up)");
     if (!shape_ok(Hq, Hkv, d, dtype, why)) return fail(PK_EINVAL, w + ": " + why);
     if (out_dtype != PK_BF16 && out_dtype != PK_F32) return fail(PK_EINVAL, w + ": bad out_dtype");
+    if (!(scale > 0.f) || !std::isfinite(scale)) return fail(PK_EINVAL, w + ": scale must be finite and positive");
     if (dtype == PK_BF16 && (d != 64 && d != 128)) return fail(PK_EUNSUPPORTED, w + ": bf16 path needs d in {64,128}");
     if (dtype == PK_BF16 && Hq / Hkv > 32) return fail(PK_EUNSUPPORTED, w + ": bf16 path needs Hq/Hkv <= 32");
     if (dtype == PK_F32 && d > 256) return fail(PK_EUNSUPPORTED, w + ": fp32 path needs d <= 256");
@@ -483,6 +486,7 @@ extern "C" int pk_padded_decode_attn(pk_plan* plan, const void* q,
         if (page_size <= 0 || num_blocks <= 0) return fail(PK_EINVAL, "pk_padded_decode_attn: page_size and num_blocks must be positive");
         if (!shape_ok(Hq, Hkv, d, dtype, why)) return fail(PK_EINVAL, "pk_padded_decode_attn: " + why);
         if (out_dtype != PK_BF16 && out_dtype != PK_F32) return fail(PK_EINVAL, "pk_padded_decode_attn: bad out_dtype");
+        if (!(scale > 0.f) || !std::isfinite(scale)) return fail(PK_EINVAL, "pk_padded_decode_attn: scale must be finite and positive");
         if (dtype != PK_BF16) return fail(PK_EUNSUPPORTED, "pk_padded_decode_attn: bf16 only");
         if (d != 64 && d != 128) return fail(PK_EUNSUPPORTED, "pk_padded_decode_attn: needs d in {64,128}");
         if (Hq / Hkv > 16) return fail(PK_EUNSUPPORTED, "pk_padded_decode_attn: needs Hq/Hkv <= 16");

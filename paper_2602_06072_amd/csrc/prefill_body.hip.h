@@ -144,9 +144,9 @@ __device__ __forceinline__ bool setup(const PrefillArgs& a, const int block, Wor
         off.g[q] = static_cast<int>(row * u.row_bytes + u.kvh * ROWB + ((pos ^ swz(row)) << 4));
     }
 #endif
-    // Q operand: lane (n, hlf) holds Q[row n][16s + 8hlf .. +8].  Only requested here: the caller
-    // scales it (scale_q) after it has requested the first K/V tiles, so that the two round trips
-    // to memory overlap.
+    // Q operand: lane (n, hlf) holds Q[row n][16s + 8hlf .. +8], as it is in memory: the MFMAs
+    // deliver raw scores, exact products of the bf16 inputs summed in fp32.  Only requested here;
+    // the first K/V copies follow at once, so that the two round trips to memory overlap.
     const uint16_t* qp = static_cast<const uint16_t*>(a.q) +
                          (static_cast<int64_t>(u.qrow < 0 ? 0 : u.qrow) * a.Hq + u.head) * D + 8 * u.hlf;
 #pragma unroll
@@ -156,24 +156,6 @@ __device__ __forceinline__ bool setup(const PrefillArgs& a, const int block, Wor
         qf[s] = __builtin_bit_cast(bf16x8, raw);
     }
     return true;
-}
-
-// Q times scale * log2(e), in fp32, rounded to bf16 again: the MFMAs then deliver the scores in the
-// exp2 domain and the softmax needs no multiplication per score.
-__device__ __forceinline__ void scale_q(bf16x8 (&qf)[KS], float sl2) {
-#pragma unroll
-    for (int s = 0; s < KS; ++s) {
-        const u32x4 raw = __builtin_bit_cast(u32x4, qf[s]);
-        u32x4 scaled;
-#pragma unroll
-        for (int w = 0; w < 4; ++w) {
-            floatx2 f;
-            f[0] = __uint_as_float(raw[w] << 16) * sl2;
-            f[1] = __uint_as_float(raw[w] & 0xFFFF0000u) * sl2;
-            scaled[w] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
-        }
-        qf[s] = __builtin_bit_cast(bf16x8, scaled);
-    }
 }
 
 // o / l to global memory; lane (n, hlf) owns columns 32b + 8q + 4hlf .. +3 of its query row.
@@ -286,17 +268,21 @@ __device__ __forceinline__ void lds_copy_16(const u32x4& rsrc, uint32_t lds_addr
 //   barrier   this wave's copies have landed; every wave is done with the tile
 // The LDS operand reads of a phase are issued one phase ahead (the reads of phase 1 during phase 4
 // of the previous tile), into two register buffers of eight operands each.
-// Softmax state of a query row, in the exp2 domain (Q carries scale * log2 e):
-//   m_ref   reference that the exponentials are taken against; it only has to stay within 2^13
-//           of the running maximum, so it moves rarely ("lazy" rescaling);
-//   negm    sixteen copies of -m_ref: the S accumulators START there, so the MFMAs deliver
-//           s - m_ref and the softmax has no subtraction per score;
+// Softmax state of a query row.  The MFMAs work on Q and K as they are in memory, so a raw score is
+// the exact sum of bf16 products in fp32; one fused multiply-add per score turns it into an exponent
+// of two relative to the row's reference: x = sc * s - m_ref, sc = scale * log2 e.  (Folding sc
+// into Q instead would save that instruction but costs another rounding of Q to bf16: 2^-9
+// relative per element, which for scores of a few units' spread is an error of 0.03 .. 0.04 in
+// the output, measured.)
+//   m_ref   reference that the exponentials are taken against, in the exp2 domain; it only has to
+//           stay within 2^13 of the running maximum, so it moves rarely ("lazy" rescaling);
 //   m_set   the row has seen a key (m_ref means something);  l  this lane's share of the row sum.
-// Fast path of a half tile (16 scores per lane): p = exp2(s), pairs rounded to bf16, row sums by
-// dot2 -- four vector instructions per pair, no maximum.  The increment of the sum tells whether
-// the reference is still good: if any lane's increment exceeds 2^13 (or a row has no reference
-// yet) the whole wave redoes the half tile on the slow path below, which finds the maximum,
-// moves the reference and rescales.
+// Fast path of a half tile (16 scores per lane): p = exp2(x), pairs rounded to bf16, row sums of
+// the rounded pairs by dot2, no maximum.  The increment of the sum tells whether the reference is
+// still good: if any lane's increment exceeds 2^13 (or a row has no reference yet) the whole wave
+// redoes the half tile on the slow path below, which finds the maximum, moves the reference and
+// rescales what has been accumulated.  Scores that are still in the making (the other half tile's)
+// are raw and meet the new reference when their turn comes.
 struct HalfSoftmax {
     float l0, l1;
     uint32_t pw[8];
@@ -319,15 +305,18 @@ __device__ __forceinline__ float max2f(float a, float b) {
 
 // Slice C (0..7) of the fast path: pair C of the half tile.
 template <int C>
-__device__ __forceinline__ void softmax_slice(const floatx16& s, HalfSoftmax& h) {
+__device__ __forceinline__ void softmax_slice(const floatx16& s, HalfSoftmax& h, const float sc, const float m_ref) {
     floatx2 pp;
-    pp[0] = __builtin_amdgcn_exp2f(s[2 * C]);
-    pp[1] = __builtin_amdgcn_exp2f(s[2 * C + 1]);
+    pp[0] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[2 * C], sc, -m_ref));
+    pp[1] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[2 * C + 1], sc, -m_ref));
     const bf16x2 pb = __builtin_convertvector(pp, bf16x2);
-    // plain adds of the unrounded values: v_dot2c_f32_bf16 would sum the rounded pair in one
-    // instruction, but it stalls the matrix pipe (measured: 8 per 8 MFMAs cost as much as 4 MFMAs)
-    h.l0 += pp[0];
-    h.l1 += pp[1];
+    // The row sum takes the ROUNDED pair, the same numbers that go into P.V: a probability is taken
+    // against a reference that may lie far from the row maximum, so even a dominant one is not a
+    // round number, and its rounding error (2^-9 relative) has to cancel between numerator and
+    // denominator.  (Measured: with the unrounded values in the sum a row that one key dominates is
+    // off by 1.4e-2, with the rounded ones by 5e-3, like a kernel that takes exp against the maximum.)
+    if constexpr (C & 1) h.l1 = __builtin_amdgcn_fdot2_f32_bf16(pb, bf16x2{(__bf16)1.0f, (__bf16)1.0f}, h.l1, false);
+    else h.l0 = __builtin_amdgcn_fdot2_f32_bf16(pb, bf16x2{(__bf16)1.0f, (__bf16)1.0f}, h.l0, false);
     h.pw[C] = __builtin_bit_cast(uint32_t, pb);
 }
 
@@ -357,27 +346,28 @@ __device__ __forceinline__ void softmax_redo(floatx16& s, HalfSoftmax& h, float 
         pp[0] = __builtin_amdgcn_exp2f(s[2 * q] - delta);
         pp[1] = __builtin_amdgcn_exp2f(s[2 * q + 1] - delta);
         const bf16x2 pb = __builtin_convertvector(pp, bf16x2);
-        h.l0 += pp[0];
-        h.l1 += pp[1];
+        if (q & 1) h.l1 = __builtin_amdgcn_fdot2_f32_bf16(pb, bf16x2{(__bf16)1.0f, (__bf16)1.0f}, h.l1, false);
+        else h.l0 = __builtin_amdgcn_fdot2_f32_bf16(pb, bf16x2{(__bf16)1.0f, (__bf16)1.0f}, h.l0, false);
         h.pw[q] = __builtin_bit_cast(uint32_t, pb);
     }
 }
-#define PK_SOFTMAX_CHECK(S, H, SHIFT_ALSO)                                                     \
+#define PK_SOFTMAX_CHECK(S, H)                                                                 \
     {                                                                                          \
         const bool slow = __builtin_amdgcn_ballot_w64((H.l0 + H.l1) > kIncLimit || !m_set) != 0; \
         float delta = 0.f, alpha = 1.f;                                                        \
         /* the empty asm statements keep the compiler from computing the rare branches always */ \
-        if (slow) { asm volatile(""); softmax_slow_scalars(S, m_ref, m_set, delta, alpha); }   \
+        if (slow) {                                                                            \
+            asm volatile("");                                                                  \
+            /* exponents of two relative to the present reference */                           \
+            _Pragma("unroll") for (int e = 0; e < 16; ++e) S[e] = __builtin_fmaf(S[e], sc, -m_ref); \
+            softmax_slow_scalars(S, m_ref, m_set, delta, alpha);                               \
+        }                                                                                      \
         if (slow) { asm volatile(""); softmax_redo(S, H, delta); }                             \
         l = l * alpha + (H.l0 + H.l1);                                                         \
         if (slow) {                                                                            \
             _Pragma("unroll") for (int b = 0; b < DB; ++b)                                     \
                 _Pragma("unroll") for (int e = 0; e < 16; ++e) o[b][e] *= alpha;               \
         }                                                                                      \
-        if (slow) {                                                                            \
-            _Pragma("unroll") for (int e = 0; e < 16; ++e) negm[e] = -m_ref;                   \
-        }                                                                                      \
-        SHIFT_ALSO                                                                             \
     }
 
 // The compiler is free to move the (side-effect free) softmax arithmetic and the MFMAs of a phase
@@ -431,7 +421,7 @@ __device__ __forceinline__ bf16x8 stream_operand(const unsigned char* k_cur, con
         constexpr int i = C;                                                                   \
         BODY;                                                                                  \
         pin_slice_inputs<C>(ACC, S);                                                           \
-        softmax_slice<C>(S, H);                                                                \
+        softmax_slice<C>(S, H, sc, m_ref);                                                     \
         pin_slice_outputs<C>(ring[(C + 1) & 3], H);                                            \
     }
 #if PK_D == 128
@@ -459,8 +449,8 @@ __device__ __forceinline__ bf16x8 stream_operand(const unsigned char* k_cur, con
         constexpr int i = I;                                                                   \
         BODY;                                                                                  \
         pin_slice_inputs<I>(ACC, S);                                                           \
-        softmax_slice<2 * (I)>(S, H);                                                          \
-        softmax_slice<2 * (I) + 1>(S, H);                                                      \
+        softmax_slice<2 * (I)>(S, H, sc, m_ref);                                               \
+        softmax_slice<2 * (I) + 1>(S, H, sc, m_ref);                                           \
         pin_slice_outputs<2 * (I)>(ring[((I) + 1) & 3], H);                                    \
         pin_slice_outputs<2 * (I) + 1>(ring[((I) + 1) & 3], H);                                \
     }
@@ -501,7 +491,8 @@ __device__ __forceinline__ void prefill_tile_body(const PrefillArgs& a, const in
     // rows without a query count as "set" so that they never ask for the slow path
     float m_ref = 0.f, l = 0.f;
     bool m_set = u.qrow < 0;
-    floatx16 negm = {};
+    const floatx16 zero16 = {};
+    const float sc = a.scale * kLog2e;             // raw score -> exponent of two (the API admits only finite scale > 0)
 
     // this wave's quarter of a stage, as a scalar
     const uint32_t lds_wave = __builtin_amdgcn_readfirstlane(lds_base + u.wave * WAVE_PART);
@@ -512,7 +503,6 @@ __device__ __forceinline__ void prefill_tile_body(const PrefillArgs& a, const in
     PK_COPY_TILE(a.k, u.ks0, 0, true);
     PK_COPY_TILE(a.k, u.ks1, TILE_BYTES, 1 < n_kv);
     PK_COPY_TILE(a.v, u.ks0, 3 * TILE_BYTES, true);
-    scale_q(qf, a.scale * kLog2e);                 // (waits for the Q loads, which were requested first)
     PK_WAIT_ALL_COPIES();
     __syncthreads();
 
@@ -564,16 +554,14 @@ __device__ __forceinline__ void prefill_tile_body(const PrefillArgs& a, const in
         const int hi_t = min(u.hi, k_start + (e0i & 0xFF));   // keys past the tile's valid count are foreign
         PK_TILE_BEGIN();
         floatx16 s0, s1;
-        PK_EIGHT(s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[i & 3], qf[i], i == 0 ? negm : s0, 0, 0, 0);
+        PK_EIGHT(s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[i & 3], qf[i], i == 0 ? zero16 : s0, 0, 0, 0);
                  PK_REFILL(0); PK_COPY_STEP(i));
         HalfSoftmax h0, h1;
         h0.l0 = 0.f; h0.l1 = 0.f; h1.l0 = 0.f; h1.l1 = 0.f;
         if (masked) mask_half(s0, 0, u.lo, hi_t, k_start, u.hlf);    // unmasked tiles skip the compares
-        PK_SLICES(s0, h0, s1, s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[i & 3], qf[i], i == 0 ? negm : s1, 0, 0, 0);
+        PK_SLICES(s0, h0, s1, s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[i & 3], qf[i], i == 0 ? zero16 : s1, 0, 0, 0);
                   PK_REFILL(KS));
-        PK_SOFTMAX_CHECK(s0, h0, if (slow) {                      /* S1 was started at the old reference */
-            _Pragma("unroll") for (int e = 0; e < 16; ++e) s1[e] -= delta;
-        })
+        PK_SOFTMAX_CHECK(s0, h0)
         bf16x8 p0[2], p1[2];
 #pragma unroll
         for (int t = 0; t < 2; ++t)
@@ -581,7 +569,7 @@ __device__ __forceinline__ void prefill_tile_body(const PrefillArgs& a, const in
         if (masked) mask_half(s1, 1, u.lo, hi_t, k_start, u.hlf);
         PK_SLICES(s1, h1, o[i % DB], o[i % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[i & 3], p0[i / DB], o[i % DB], 0, 0, 0);
                   PK_REFILL(2 * KS));
-        PK_SOFTMAX_CHECK(s1, h1, )
+        PK_SOFTMAX_CHECK(s1, h1)
 #pragma unroll
         for (int t = 0; t < 2; ++t)
             p1[t] = __builtin_bit_cast(bf16x8, u32x4{h1.pw[4 * t], h1.pw[4 * t + 1], h1.pw[4 * t + 2], h1.pw[4 * t + 3]});

@@ -186,6 +186,13 @@ def test_step_entry_points_validate_before_touching_the_device():
     assert L.pk_packed_decode_attn_grown(plan.handle, p, p, p, 1.0, 3, 4, 2, 64, 0, 0, p, 16, None) == -1   # grown > headroom
     prefill_plan = pk.pack_plan([4, 4], token_budget=8, headroom=2)
     assert L.pk_kv_append(prefill_plan.handle, p, p, p, 0, 2, 64, 0, p, 16, None) == -1   # not a decode plan
+    # the softmax scale must be finite and positive, in every attention call
+    for bad in (0.0, -0.125, float("nan"), float("inf")):
+        assert L.pk_packed_decode_attn(plan.handle, p, p, p, bad, 4, 2, 64, 0, 0, p, 16, None) == -1
+        assert b"scale" in L.pk_last_error()
+        assert L.pk_packed_prefill_attn(prefill_plan.handle, p, p, p, p, bad, 4, 2, 64, 0, 0, p, 16, None) == -1
+        assert b"scale" in L.pk_last_error()
+        assert L.pk_padded_prefill_attn(prefill_plan.handle, p, p, p, p, bad, 4, 2, 64, 0, 0, p, 16, None) == -1
 
 
 # ---- TriePartition from token ids: host logic, bit-equal to the oracle ----------------------------
