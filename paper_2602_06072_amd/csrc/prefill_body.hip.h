@@ -303,18 +303,24 @@ __device__ __forceinline__ float max2f(float a, float b) {
     return r;
 }
 
-// Slice C (0..7) of the fast path: pair C of the half tile.
+// Slice C (0..7) of the fast path: pair C of the half tile, in two stages, so that the conversion
+// never waits for its exponentials: stage A (fma, exp) right behind MFMA C, stage B (round, sum,
+// pack) behind MFMA C + 1 (1.4 % on the whole kernel; a third stage between fma and exp: nothing).
+// The row sum takes the ROUNDED pair, the same numbers that go into P.V: a probability is taken
+// against a reference that may lie far from the row maximum, so even a dominant one is not a round
+// number, and its rounding error (2^-9 relative) has to cancel between numerator and denominator.
+// (Measured: with the unrounded values in the sum a row that one key dominates is off by 1.4e-2,
+// with the rounded ones by 5e-3, like a kernel that takes exp against the maximum.)
 template <int C>
-__device__ __forceinline__ void softmax_slice(const floatx16& s, HalfSoftmax& h, const float sc, const float m_ref) {
+__device__ __forceinline__ floatx2 slice_a(const floatx16& s, const float sc, const float m_ref) {
     floatx2 pp;
     pp[0] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[2 * C], sc, -m_ref));
     pp[1] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[2 * C + 1], sc, -m_ref));
+    return pp;
+}
+template <int C>
+__device__ __forceinline__ void slice_b(const floatx2 pp, HalfSoftmax& h) {
     const bf16x2 pb = __builtin_convertvector(pp, bf16x2);
-    // The row sum takes the ROUNDED pair, the same numbers that go into P.V: a probability is taken
-    // against a reference that may lie far from the row maximum, so even a dominant one is not a
-    // round number, and its rounding error (2^-9 relative) has to cancel between numerator and
-    // denominator.  (Measured: with the unrounded values in the sum a row that one key dominates is
-    // off by 1.4e-2, with the rounded ones by 5e-3, like a kernel that takes exp against the maximum.)
     if constexpr (C & 1) h.l1 = __builtin_amdgcn_fdot2_f32_bf16(pb, bf16x2{(__bf16)1.0f, (__bf16)1.0f}, h.l1, false);
     else h.l0 = __builtin_amdgcn_fdot2_f32_bf16(pb, bf16x2{(__bf16)1.0f, (__bf16)1.0f}, h.l0, false);
     h.pw[C] = __builtin_bit_cast(uint32_t, pb);
@@ -421,15 +427,21 @@ __device__ __forceinline__ bf16x8 stream_operand(const unsigned char* k_cur, con
         constexpr int i = C;                                                                   \
         BODY;                                                                                  \
         pin_slice_inputs<C>(ACC, S);                                                           \
-        softmax_slice<C>(S, H, sc, m_ref);                                                     \
-        pin_slice_outputs<C>(ring[(C + 1) & 3], H);                                            \
+        if constexpr (C > 0) slice_b<(C > 0 ? C - 1 : 0)>(pend, H);                            \
+        pend = slice_a<C>(S, sc, m_ref);                                                       \
+        asm volatile("" : "+v"(pend));                                                         \
+        pin_slice_outputs<(C > 0 ? C - 1 : 0)>(ring[(C + 1) & 3], H);                          \
     }
 #if PK_D == 128
 // eight MFMAs (BODY, with accumulator ACC) interleaved with the softmax of the scores S
 #define PK_SLICES(S, H, ACC, BODY)                                                             \
+    {                                                                                          \
+    floatx2 pend;                                                                              \
     PK_SLICE(0, S, H, ACC, BODY) PK_SLICE(1, S, H, ACC, BODY) PK_SLICE(2, S, H, ACC, BODY)       \
     PK_SLICE(3, S, H, ACC, BODY) PK_SLICE(4, S, H, ACC, BODY) PK_SLICE(5, S, H, ACC, BODY)       \
-    PK_SLICE(6, S, H, ACC, BODY) PK_SLICE(7, S, H, ACC, BODY)
+    PK_SLICE(6, S, H, ACC, BODY) PK_SLICE(7, S, H, ACC, BODY)                                    \
+    slice_b<7>(pend, H);                                                                       \
+    }
 
 #define PK_EIGHT(BODY)                                                                         \
     {                                                                                          \
@@ -449,14 +461,24 @@ __device__ __forceinline__ bf16x8 stream_operand(const unsigned char* k_cur, con
         constexpr int i = I;                                                                   \
         BODY;                                                                                  \
         pin_slice_inputs<I>(ACC, S);                                                           \
-        softmax_slice<2 * (I)>(S, H, sc, m_ref);                                               \
-        softmax_slice<2 * (I) + 1>(S, H, sc, m_ref);                                           \
-        pin_slice_outputs<2 * (I)>(ring[((I) + 1) & 3], H);                                    \
-        pin_slice_outputs<2 * (I) + 1>(ring[((I) + 1) & 3], H);                                \
+        if constexpr ((I) > 0) {                                                               \
+            slice_b<((I) > 0 ? 2 * (I) - 2 : 0)>(pend, H);                                     \
+            slice_b<((I) > 0 ? 2 * (I) - 1 : 1)>(pend2, H);                                    \
+        }                                                                                      \
+        pend = slice_a<2 * (I)>(S, sc, m_ref);                                                 \
+        pend2 = slice_a<2 * (I) + 1>(S, sc, m_ref);                                            \
+        asm volatile("" : "+v"(pend), "+v"(pend2));                                            \
+        pin_slice_outputs<((I) > 0 ? 2 * (I) - 2 : 0)>(ring[((I) + 1) & 3], H);                \
+        pin_slice_outputs<((I) > 0 ? 2 * (I) - 1 : 1)>(ring[((I) + 1) & 3], H);                \
     }
 #define PK_SLICES(S, H, ACC, BODY)                                                             \
+    {                                                                                          \
+    floatx2 pend, pend2;                                                                       \
     PK_SLICE2(0, S, H, ACC, BODY) PK_SLICE2(1, S, H, ACC, BODY) PK_SLICE2(2, S, H, ACC, BODY)    \
-    PK_SLICE2(3, S, H, ACC, BODY)
+    PK_SLICE2(3, S, H, ACC, BODY)                                                              \
+    slice_b<6>(pend, H);                                                                       \
+    slice_b<7>(pend2, H);                                                                      \
+    }
 
 #define PK_EIGHT(BODY)                                                                         \
     {                                                                                          \
