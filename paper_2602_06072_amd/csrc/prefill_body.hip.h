@@ -266,8 +266,8 @@ __device__ __forceinline__ void lds_copy_16(const u32x4& rsrc, uint32_t lds_addr
 //   phase 3   O += V(half 0)^T P0^T   with the softmax of S1       (8 MFMAs + vector work)
 //   phase 4   O += V(half 1)^T P1^T                                (8 MFMAs)
 //   barrier   this wave's copies have landed; every wave is done with the tile
-// The LDS operand reads of a phase are issued one phase ahead (the reads of phase 1 during phase 4
-// of the previous tile), into two register buffers of eight operands each.
+// The LDS operand reads run four MFMAs ahead, in a ring of four operand registers that carries over
+// the tile boundary (the first operands of tile j + 1 are read during the last MFMAs of tile j).
 // Softmax state of a query row.  The MFMAs work on Q and K as they are in memory, so a raw score is
 // the exact sum of bf16 products in fp32; one fused multiply-add per score turns it into an exponent
 // of two relative to the row's reference: x = sc * s - m_ref, sc = scale * log2 e.  (Folding sc
@@ -412,8 +412,9 @@ __device__ __forceinline__ bf16x8 v_operand_x(const unsigned char* vs, const Lan
     return v_operand(vs, lo, half, x / DB, x % DB);
 }
 // Operand stream of a tile (KS operands per half tile; shown for D = 128): 0..7 K(half 0), 8..15
-// K(half 1), 16..23 V(half 0), 24..31 V(half 1), 32..35 the first K operands of the next tile.  MFMA k takes ring[k % 4] and then refills that
-// slot with operand k + 4, so that every LDS read has four MFMAs (and their vector slices) to land.
+// K(half 1), 16..23 V(half 0), 24..31 V(half 1), 32..35 the first K operands of the next tile.
+// MFMA k takes ring[k % 4] and then refills that slot with operand k + 4, so that every LDS read
+// has four MFMAs (and their vector slices) to land.
 template <int K>
 __device__ __forceinline__ bf16x8 stream_operand(const unsigned char* k_cur, const unsigned char* v_cur,
                                                  const unsigned char* k_next, const LaneOffsets& off) {
