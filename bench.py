@@ -571,6 +571,13 @@ def bench_mixed(w5, steps, warmup, with_padded=True):
                 "fused_over_separate": fused_ms / (prefill_ms + decode_ms)})
     if with_padded:
         pk.plan_bind(plan_p0, p.Hq, p.Hkv, p.d, pk.PK_BF16, ws_p)
+        # the packed prefill launch on all-zero inputs: the same instructions with nothing toggling in the
+        # operands, i.e. what the schedule reaches when the power-managed clock does not come down
+        zq, zk = torch.zeros_like(p.q), torch.zeros_like(p.k)
+        zero_ms, _ = _time_launches(lambda: pk.packed_prefill_attn(plan_p0, zq, zk, zk, out_p, p.scale, ws_p), 5, warmup=1)
+        del zq, zk
+        res.update({"prefill_kernel_ms_on_all_zero_inputs": zero_ms,
+                    "prefill_kernel_tflops_on_all_zero_inputs": flops / (zero_ms * 1e-3) / 1e12})
         pad_p, _ = _time_launches(lambda: pk.padded_prefill_attn(plan_p0, p.q, p.k, p.v, out_p, p.scale, ws_p), 5, warmup=1)
         pad_d, _ = _time_launches(lambda: pk.padded_decode_attn(plan_d0, d.q, d.k_pages, d.v_pages, bt, out_d, d.scale, ws_d), 5, warmup=1)
         res.update({"padded_prefill_kernel_ms": pad_p, "padded_decode_ms": pad_d,
