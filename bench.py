@@ -483,7 +483,7 @@ def motivation_replay(wl, pk, seed, dev):
     return res
 
 
-def bench_mixed(w5, steps, warmup, with_padded=True):
+def bench_mixed(w5, steps, warmup, with_padded=True, zero_inputs=True):
     """The mixed step of configuration 5: every row of the hot path once per step, kernels timed with HIP
     events on the launch stream inside the timed steps."""
     import torch
@@ -573,11 +573,12 @@ def bench_mixed(w5, steps, warmup, with_padded=True):
         pk.plan_bind(plan_p0, p.Hq, p.Hkv, p.d, pk.PK_BF16, ws_p)
         # the packed prefill launch on all-zero inputs: the same instructions with nothing toggling in the
         # operands, i.e. what the schedule reaches when the power-managed clock does not come down
-        zq, zk = torch.zeros_like(p.q), torch.zeros_like(p.k)
-        zero_ms, _ = _time_launches(lambda: pk.packed_prefill_attn(plan_p0, zq, zk, zk, out_p, p.scale, ws_p), 5, warmup=1)
-        del zq, zk
-        res.update({"prefill_kernel_ms_on_all_zero_inputs": zero_ms,
-                    "prefill_kernel_tflops_on_all_zero_inputs": flops / (zero_ms * 1e-3) / 1e12})
+        if zero_inputs:
+            zq, zk = torch.zeros_like(p.q), torch.zeros_like(p.k)
+            zero_ms, _ = _time_launches(lambda: pk.packed_prefill_attn(plan_p0, zq, zk, zk, out_p, p.scale, ws_p), 5, warmup=1)
+            del zq, zk
+            res.update({"prefill_kernel_ms_on_all_zero_inputs": zero_ms,
+                        "prefill_kernel_tflops_on_all_zero_inputs": flops / (zero_ms * 1e-3) / 1e12})
         pad_p, _ = _time_launches(lambda: pk.padded_prefill_attn(plan_p0, p.q, p.k, p.v, out_p, p.scale, ws_p), 5, warmup=1)
         pad_d, _ = _time_launches(lambda: pk.padded_decode_attn(plan_d0, d.q, d.k_pages, d.v_pages, bt, out_d, d.scale, ws_d), 5, warmup=1)
         res.update({"padded_prefill_kernel_ms": pad_p, "padded_decode_ms": pad_d,
@@ -652,6 +653,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-extras", action="store_true", help="only the headline workload")
+    ap.add_argument("--no-zero-inputs", action="store_true",
+                    help="skip the prefill launch on all-zero inputs (profiling runs: it would mix into the kernel's average)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain elementwise kernel over 1 GiB 5 times (reference for HBM byte counters)")
@@ -702,7 +705,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     w5 = wl.config5(args.seed, device=dev)
-    m = bench_mixed(w5, args.steps, args.warmup)
+    m = bench_mixed(w5, args.steps, args.warmup, zero_inputs=not args.no_zero_inputs)
     line = {
         "metric": "packed attn prefill TFLOP/s + decode KV GB/s (% roofline) vs padded",
         "value": m["step_tflops"], "unit": "TFLOP/s",
