@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the packed-attention hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--seed S] [--no-extras]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--seed S] [--no-extras] [--no-cpu] [--no-zero-inputs]
 
 Prints ONE JSON line.  Headline workload: the mixed continuous-batching step of
 the Llama-3-70B-shaped attention layer (configs[4]: 64 query / 8 KV heads,
