@@ -257,7 +257,7 @@ int pk_packed_decode_attn(pk_plan* plan, const void* q, const void* kv_buf,
  *   scale, Hq, Hkv, d, dtype, out_dtype: common to both halves (one layer)
  * A plan with n = 0 makes the call equal to the other half's own call.
  * Errors: as for the two calls; PK_EUNSUPPORTED unless dtype is PK_BF16 and
- * d = 128. */
+ * d is 64 or 128. */
 int pk_packed_mixed_step(pk_plan* prefill_plan, const void* q, const void* k, const void* v, void* out,
                          void* prefill_workspace, size_t prefill_workspace_bytes,
                          pk_plan* decode_plan, const void* decode_q, const void* kv_buf, void* decode_out,

@@ -380,8 +380,8 @@ extern "C" int pk_packed_mixed_step(pk_plan* prefill_plan, const void* q, const 
     return pk::guarded<int>(PK_ENOMEM, PK_EINVAL, "pk_packed_mixed_step", [&]() -> int {
         const char* who = "pk_packed_mixed_step";
         if (!prefill_plan || !decode_plan) return fail(PK_EINVAL, "pk_packed_mixed_step: plan is NULL");
-        if (dtype != PK_BF16 || d != 128)
-            return fail(PK_EUNSUPPORTED, "pk_packed_mixed_step: the fused launch is built for bf16 and d = 128 "
+        if (dtype != PK_BF16 || (d != 128 && d != 64))
+            return fail(PK_EUNSUPPORTED, "pk_packed_mixed_step: the fused launch is built for bf16 and d in {64,128} "
                                          "(call pk_packed_prefill_attn and pk_packed_decode_attn otherwise)");
         if (prefill_workspace && prefill_workspace == decode_workspace)
             return fail(PK_EINVAL, "pk_packed_mixed_step: the two plans need a workspace each");

@@ -15,6 +15,11 @@
 #include "prefill_body.hip.h"
 #undef PK_D
 #undef PK_DNS
+#define PK_D 64
+#define PK_DNS d64
+#include "prefill_body.hip.h"
+#undef PK_D
+#undef PK_DNS
 
 namespace pk {
 namespace {
@@ -24,33 +29,38 @@ namespace {
 // every unit one of each (as long as both kinds last).
 constexpr int kRun = 256;
 
-__global__ __launch_bounds__(256, 2) void mixed_step_kernel(PrefillArgs pa, DecodeArgs da, int n_prefill_blocks,
-                                                            int n_decode_blocks) {
-    __shared__ __align__(1024) unsigned char lds[5 * d128::TILE_BYTES];
-    const int x = static_cast<int>(blockIdx.x);
-    const int decode_groups = (n_decode_blocks + kRun - 1) / kRun;
-    int prefill_block;
-    if (x / (2 * kRun) < decode_groups) {
-        const int grp = x / (2 * kRun), pos = x % (2 * kRun);
-        if (pos >= kRun) {                          // a decode workgroup: four (work item, KV head) pairs
-            const int unit = ((grp * kRun + pos - kRun) * 4) + static_cast<int>(threadIdx.x >> 6);
-            const int item = unit / da.Hkv, kvh = unit % da.Hkv;
-            if (item >= da.n_items) return;
-            if (item < da.n_wide) decode_body<128, 2, 2>(da, item, kvh);
-            else decode_body<128, 1, 1>(da, item, kvh);
-            return;
-        }
-        prefill_block = grp * kRun + pos;
-    } else {
-        prefill_block = x - decode_groups * kRun;
+// one kernel per head dimension (NS: the namespace of the prefill body, D: the head dimension)
+#define PK_MIXED_STEP_KERNEL(NAME, NS, D)                                                            \
+    __global__ __launch_bounds__(256, 2) void NAME(PrefillArgs pa, DecodeArgs da, int n_prefill_blocks, \
+                                                   int n_decode_blocks) {                            \
+        __shared__ __align__(1024) unsigned char lds[5 * NS::TILE_BYTES];                             \
+        const int x = static_cast<int>(blockIdx.x);                                                  \
+        const int decode_groups = (n_decode_blocks + kRun - 1) / kRun;                               \
+        int prefill_block;                                                                           \
+        if (x / (2 * kRun) < decode_groups) {                                                        \
+            const int grp = x / (2 * kRun), pos = x % (2 * kRun);                                    \
+            if (pos >= kRun) { /* a decode workgroup: four (work item, KV head) pairs */              \
+                const int unit = ((grp * kRun + pos - kRun) * 4) + static_cast<int>(threadIdx.x >> 6); \
+                const int item = unit / da.Hkv, kvh = unit % da.Hkv;                                 \
+                if (item >= da.n_items) return;                                                      \
+                if (item < da.n_wide) decode_body<D, 2, 2>(da, item, kvh);                           \
+                else decode_body<D, 1, 1>(da, item, kvh);                                            \
+                return;                                                                              \
+            }                                                                                        \
+            prefill_block = grp * kRun + pos;                                                        \
+        } else {                                                                                     \
+            prefill_block = x - decode_groups * kRun;                                                \
+        }                                                                                            \
+        if (prefill_block >= n_prefill_blocks) return;                                               \
+        NS::prefill_tile_body(pa, prefill_block, lds);                                               \
     }
-    if (prefill_block >= n_prefill_blocks) return;
-    d128::prefill_tile_body(pa, prefill_block, lds);
-}
+PK_MIXED_STEP_KERNEL(mixed_step_kernel, d128, 128)
+PK_MIXED_STEP_KERNEL(mixed_step64_kernel, d64, 64)
+#undef PK_MIXED_STEP_KERNEL
 
 }  // namespace
 
-// d = 128, bf16.  Returns a hipError_t as int.
+// bf16, d = 128 or 64.  Returns a hipError_t as int.
 int launch_mixed_step_bf16(const PrefillArgs& pa, const DecodeArgs& da, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int r = pa.Hq / pa.Hkv;
@@ -63,9 +73,15 @@ int launch_mixed_step_bf16(const PrefillArgs& pa, const DecodeArgs& da, void* st
     // decode groups the stretch is padded with workgroups that exit at once
     const int64_t grid = decode_groups * 2 * kRun + (n_prefill > decode_groups * kRun ? n_prefill - decode_groups * kRun : 0);
     if (grid > 0x7FFFFFFF) return static_cast<int>(hipErrorInvalidValue);
-    if (grid > 0)
-        hipLaunchKernelGGL(mixed_step_kernel, dim3(static_cast<unsigned>(grid)), dim3(256), 0, st, pa, da,
-                           static_cast<int>(n_prefill), static_cast<int>(n_decode));
+    if (pa.d != da.d || (pa.d != 128 && pa.d != 64)) return static_cast<int>(hipErrorInvalidValue);
+    if (grid > 0) {
+        if (pa.d == 128)
+            hipLaunchKernelGGL(mixed_step_kernel, dim3(static_cast<unsigned>(grid)), dim3(256), 0, st, pa, da,
+                               static_cast<int>(n_prefill), static_cast<int>(n_decode));
+        else
+            hipLaunchKernelGGL(mixed_step64_kernel, dim3(static_cast<unsigned>(grid)), dim3(256), 0, st, pa, da,
+                               static_cast<int>(n_prefill), static_cast<int>(n_decode));
+    }
     const int e = static_cast<int>(hipGetLastError());
     if (e != 0) return e;
     return launch_decode_merge_bf16(da, stream);

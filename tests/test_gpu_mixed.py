@@ -33,7 +33,7 @@ def run_both(p, d, budget_p, budget_d, out_dtype=torch.float32):
     return fus_p, fus_d
 
 
-@pytest.mark.parametrize("case", ["more_prefill", "more_decode", "families"])
+@pytest.mark.parametrize("case", ["more_prefill", "more_decode", "families", "d64", "d64_families"])
 def test_mixed_step_small(case):
     kwp = dict(seed=80, n=7, lo=5, hi=300, Hq=8, Hkv=2, d=128, token_budget=400, ctx_hi=200, device=DEV, keep_f32=False)
     kwd = dict(seed=81, n=9, lo=1, hi=500, Hq=8, Hkv=2, d=128, token_budget=900, device=DEV, keep_f32=False)
@@ -42,6 +42,12 @@ def test_mixed_step_small(case):
         kwd.update(n=60, hi=900)
     elif case == "families":
         kwd.update(n=30, families=3, prefix_lo=40, prefix_hi=300)
+    elif case == "d64":
+        kwp.update(d=64)
+        kwd.update(d=64)
+    elif case == "d64_families":
+        kwp.update(d=64, n=12, hi=700)
+        kwd.update(d=64, n=40, families=4, prefix_lo=40, prefix_hi=300)
     p, d = wl.small_ragged(**kwp), wl.small_paged(**kwd)
     fus_p, fus_d = run_both(p, d, p.token_budget, d.token_budget)
     H.assert_close(fus_p.cpu().numpy(), H.oracle_ragged(p, False), 0, f"mixed step {case}: prefill half")
